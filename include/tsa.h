@@ -1,0 +1,142 @@
+/*
+ * libtsa -- Token Sparse Attention prefill hot path for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every tensor argument is a DEVICE pointer owned by the caller, 16-byte
+ * aligned, contiguous row-major in the stated shape; bf16 tensors are passed as
+ * `const void*` / `void*` (2 bytes per element).  The library never allocates or
+ * frees device memory: scratch space comes in through the `ws` argument, sized
+ * with tsa_workspace_bytes().  All work is queued asynchronously on `stream`
+ * (a hipStream_t passed as void*, NULL = the default stream); no call
+ * synchronises with the host, and buffers must stay valid until the stream has
+ * finished the work.
+ *
+ * Every entry point returns a status code.  Arguments are validated on the
+ * host before anything is launched; on error nothing has been queued and
+ * tsa_last_error() (thread-local) describes the problem.  Inputs must be
+ * finite; behaviour for NaN / Inf inputs is undefined.
+ *
+ * Notation follows the paper: B batch, Hq query heads, Hkv key/value heads
+ * (g = Hq / Hkv query heads share a KV head: query head h reads KV head h / g),
+ * L tokens, d head dimension, S_h the per-head index set, k_keep = |S_h| = L'.
+ */
+#ifndef TSA_H
+#define TSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  TSA_OK = 0,
+  TSA_ERR_ARG = 1,          /* null / misaligned pointer, size out of range */
+  TSA_ERR_UNSUPPORTED = 2,  /* valid request this build has no kernel for */
+  TSA_ERR_WORKSPACE = 3,    /* ws == NULL or ws_bytes too small */
+  TSA_ERR_HIP = 4           /* a HIP launch or query failed */
+};
+
+/* Problem statement of one attention layer (Section 2.2 of the paper: per-head
+ * Q, K, V of L tokens) plus the parameters of Algorithm 1 the paper leaves open. */
+typedef struct tsa_desc {
+  int32_t B;            /* batch, >= 1 */
+  int32_t Hq;           /* query heads */
+  int32_t Hkv;          /* key/value heads, Hq % Hkv == 0 */
+  int32_t L;            /* tokens, >= 1 */
+  int32_t d;            /* head dimension: 64 or 128 */
+  int32_t last_q;       /* number of most recent queries used for scoring (Algorithm 1), 1..min(L,128) */
+  int32_t pool_w;       /* pooling width of Algorithm 1's pooling(.): only 1 (no pooling) is built */
+  int32_t group_mode;   /* 0: every query head selects its own S_h; 1: the g heads of a KV group share
+                           one set chosen from the sum of their scores */
+  int32_t force_first;  /* tokens t < force_first are always kept (score treated as +inf); default 0 */
+  int32_t force_last;   /* tokens t >= L - force_last are always kept; default 0 */
+  float   scale;        /* softmax scale; 0 means 1/sqrt(d) */
+} tsa_desc;
+
+/* Version of this ABI (increases when a signature changes). */
+int tsa_version(void);
+
+/* Text of the last error on the calling thread ("" if none).  Host pointer, owned by the library. */
+const char* tsa_last_error(void);
+
+/* Fixed token-sparsity ratio (the "fixed sparsity" policy the paper compares against in
+ * its dynamic-vs-fixed table): drop floor(tau * L) tokens.  Returns k_keep = L - floor(tau*L)
+ * clamped to [1, L]; returns 0 if L < 1 or tau is outside [0, 1]. */
+int32_t tsa_keep_count(int32_t L, double tau);
+
+/* Bytes of workspace that any entry point below needs for this problem and k_keep
+ * (tsa_forward needs the most: scores, index sets, compacted Q/K/V and output).
+ * Returns 0 if the descriptor or k_keep is invalid. */
+size_t tsa_workspace_bytes(const tsa_desc* desc, int32_t k_keep);
+
+/* Token scoring -- Algorithm 1, first two steps: A = softmax(Q[-last_q:] K^T * scale) with
+ * query i seeing keys t <= i, then the column sums s[b,h,t] = sum_i A[i,t].
+ *   Q      [B,Hq,L,d]  bf16, device (only the last last_q rows of each head are read)
+ *   K      [B,Hkv,L,d] bf16, device
+ *   scores [B,Hq,L]    fp32, device, fully overwritten
+ * Arithmetic: bf16 products accumulated in fp32 (MFMA), exact two-pass softmax in fp32. */
+int tsa_score(const tsa_desc* desc, const void* Q, const void* K, float* scores,
+              void* ws, size_t ws_bytes, void* stream);
+
+/* Top-k selection -- Algorithm 1, last step, S_h = TopK(s_h, k_keep): for every (b, hs)
+ * the k_keep tokens of largest score, ties to the lowest token index, written in ascending
+ * token order.  hs runs over Hs = Hq heads (group_mode 0) or Hs = Hkv groups (group_mode 1,
+ * where the g heads' scores are summed first, in head order, in fp32).
+ *   scores [B,Hq,L]  fp32, device
+ *   idx    [B,Hs,k_keep] int32, device, out: S_h ascending
+ *   inv    [B,Hs,L]  int32, device, out (may be NULL): inv[t] = r if idx[r] == t, else -1 */
+int tsa_select(const tsa_desc* desc, const float* scores, int32_t k_keep,
+               int32_t* idx, int32_t* inv, void* ws, size_t ws_bytes, void* stream);
+
+/* Stage 1, compression: gather the rows S_h of Q, K, V into dense contiguous tensors.
+ *   idx [B,Hs,k_keep] int32 (from tsa_select)
+ *   Qc  [B,Hq,k_keep,d] out.  group_mode 0: Kc, Vc [B,Hq,k_keep,d] (row idx[b,h,r] of KV head h/g);
+ *                             group_mode 1: Kc, Vc [B,Hkv,k_keep,d].
+ * Bit-exact row copies.  Index values must lie in [0, L). */
+int tsa_compress(const tsa_desc* desc, const void* Q, const void* K, const void* V,
+                 const int32_t* idx, int32_t k_keep, void* Qc, void* Kc, void* Vc, void* stream);
+
+/* Attention in the compressed space (Stage 1, last step; cost O(L'^2 d)): causal softmax
+ * attention over Lc rows, row r attending to columns c <= r.  Because S_h is ascending this
+ * is causal in the original positions, i.e. the hard mask of Stage 2.
+ *   Qc [B,Hq,Lc,d] bf16;  Kc, Vc [B,kv_heads,Lc,d] bf16 with Hq % kv_heads == 0
+ *   Oc [B,Hq,Lc,d] bf16 out;  lse [B,Hq,Lc] fp32 out or NULL (natural-log sum-exp of the scaled logits)
+ *   block_list: NULL for plain causal attention.  Otherwise [ceil(Lc/block_size), max_blocks_per_row]
+ *   int32 on the device, shared by all heads: row qb lists, in ascending order and padded with -1,
+ *   the key blocks that query block qb may see (composition with a block-sparse pattern in
+ *   compacted index space, Section 1 / Appendix "other sparse attention methods").  Entries > qb
+ *   are ignored; the diagonal block is causal inside.  block_size must be 128.
+ * The dense baseline is this same call with Qc=Q, Kc=K, Vc=V, Lc=L, kv_heads=Hkv.
+ * Arithmetic: bf16 MFMA with fp32 accumulation, online softmax in fp32, probabilities rounded
+ * to bf16 before the PV product, output rounded to bf16 (nearest even). */
+int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void* Vc,
+               int32_t Lc, int32_t kv_heads,
+               const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
+               void* Oc, float* lse, void* stream);
+
+/* Stage 2, decompression: scatter the compressed output back to the full sequence.
+ *   Oc  [B,Hq,k_keep,d] bf16;  idx [B,Hs,k_keep];  inv [B,Hs,L] (both from tsa_select)
+ *   O   [B,Hq,L,d] bf16 out or NULL: O[b,h,t,:] = Oc[b,h,inv[t],:] if inv[t] >= 0 else 0; every
+ *       element is written, the caller need not clear it.
+ *   residual [B,L,Hq*d] bf16 in/out or NULL: residual[b,t,h*d:(h+1)*d] += Oc[b,h,r,:] for
+ *       t = idx[r] (fp32 add, one rounding to bf16); rows of unselected tokens are untouched.  This is
+ *       the residual connection of Stage 2 with the identity in place of the output projection.
+ * At least one of O, residual must be non-NULL. */
+int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, const int32_t* inv,
+                   int32_t k_keep, void* O, void* residual, void* stream);
+
+/* The whole layer on one stream, no host synchronisation:
+ * score -> select -> compress -> attend -> decompress (Figure 3 of the paper).
+ *   Q [B,Hq,L,d], K, V [B,Hkv,L,d] bf16;  O [B,Hq,L,d] bf16 out (or NULL when only residual is wanted)
+ *   idx_out [B,Hs,k_keep] int32 out or NULL;  residual as in tsa_decompress or NULL
+ *   block_list / block_size / max_blocks_per_row as in tsa_attend (NULL, 0, 0 for plain causal) */
+int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* V, int32_t k_keep,
+                const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
+                void* O, void* residual, int32_t* idx_out,
+                void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSA_H */

@@ -1,0 +1,157 @@
+"""Thin ctypes binding of libtsa.so: same names as the C ABI (include/tsa.h), argument
+marshalling only.  Tensors are torch CUDA tensors used purely as device memory; every step
+runs in the library's HIP kernels.  There is no fallback: if the library is missing or a
+call fails, an exception is raised."""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+
+import torch
+
+from . import build as _build
+
+TSA_OK, TSA_ERR_ARG, TSA_ERR_UNSUPPORTED, TSA_ERR_WORKSPACE, TSA_ERR_HIP = 0, 1, 2, 3, 4
+
+EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_bytes", "tsa_score",
+           "tsa_select", "tsa_compress", "tsa_attend", "tsa_decompress", "tsa_forward")
+
+
+class TsaError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("libtsa error %d: %s" % (code, msg))
+        self.code = code
+
+
+class tsa_desc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("L", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("last_q", ctypes.c_int32), ("pool_w", ctypes.c_int32),
+                ("group_mode", ctypes.c_int32), ("force_first", ctypes.c_int32), ("force_last", ctypes.c_int32),
+                ("scale", ctypes.c_float)]
+
+
+def make_desc(B, Hq, Hkv, L, d, last_q=64, pool_w=1, group_mode=0, force_first=0, force_last=0, scale=0.0):
+    return tsa_desc(B, Hq, Hkv, L, d, last_q, pool_w, group_mode, force_first, force_last, scale)
+
+
+_lib = None
+
+
+def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
+    """Loads the in-tree libtsa.so; builds it first only if it does not exist."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIB_PATH
+    if not os.path.exists(path):
+        if not build_if_missing:
+            raise ImportError("libtsa.so is not built (%s)" % path)
+        _build.build_library()
+    lib = ctypes.CDLL(path)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    dp = ctypes.POINTER(tsa_desc)
+    lib.tsa_version.restype = ctypes.c_int
+    lib.tsa_version.argtypes = []
+    lib.tsa_last_error.restype = ctypes.c_char_p
+    lib.tsa_last_error.argtypes = []
+    lib.tsa_keep_count.restype = i32
+    lib.tsa_keep_count.argtypes = [i32, ctypes.c_double]
+    lib.tsa_workspace_bytes.restype = sz
+    lib.tsa_workspace_bytes.argtypes = [dp, i32]
+    lib.tsa_score.restype = ctypes.c_int
+    lib.tsa_score.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+    lib.tsa_select.restype = ctypes.c_int
+    lib.tsa_select.argtypes = [dp, vp, i32, vp, vp, vp, sz, vp]
+    lib.tsa_compress.restype = ctypes.c_int
+    lib.tsa_compress.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.tsa_attend.restype = ctypes.c_int
+    lib.tsa_attend.argtypes = [dp, vp, vp, vp, i32, i32, vp, i32, i32, vp, vp, vp]
+    lib.tsa_decompress.restype = ctypes.c_int
+    lib.tsa_decompress.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp]
+    lib.tsa_forward.restype = ctypes.c_int
+    lib.tsa_forward.argtypes = [dp, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc):
+    if rc != TSA_OK:
+        raise TsaError(rc, load_library().tsa_last_error().decode())
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TsaError(TSA_ERR_ARG, "tensor is not on the GPU")
+    if not t.is_contiguous():
+        raise TsaError(TSA_ERR_ARG, "tensor is not contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    return _ptr(ws), ws.numel() * ws.element_size()
+
+
+def tsa_version() -> int:
+    return load_library().tsa_version()
+
+
+def tsa_last_error() -> str:
+    return load_library().tsa_last_error().decode()
+
+
+def tsa_keep_count(L: int, tau: float) -> int:
+    return load_library().tsa_keep_count(L, tau)
+
+
+def tsa_workspace_bytes(desc: tsa_desc, k_keep: int) -> int:
+    return load_library().tsa_workspace_bytes(ctypes.byref(desc), k_keep)
+
+
+def tsa_score(desc, Q, K, scores, ws):
+    p, n = _ws(ws)
+    _check(load_library().tsa_score(ctypes.byref(desc), _ptr(Q), _ptr(K), _ptr(scores), p, n, _stream()))
+
+
+def tsa_select(desc, scores, k_keep, idx, inv, ws=None):
+    p, n = _ws(ws)
+    _check(load_library().tsa_select(ctypes.byref(desc), _ptr(scores), k_keep, _ptr(idx), _ptr(inv), p, n, _stream()))
+
+
+def tsa_compress(desc, Q, K, V, idx, k_keep, Qc, Kc, Vc):
+    _check(load_library().tsa_compress(ctypes.byref(desc), _ptr(Q), _ptr(K), _ptr(V), _ptr(idx), k_keep,
+                                       _ptr(Qc), _ptr(Kc), _ptr(Vc), _stream()))
+
+
+def tsa_attend(desc, Qc, Kc, Vc, Lc, kv_heads, Oc, lse=None, block_list=None, block_size=0, max_blocks_per_row=0):
+    _check(load_library().tsa_attend(ctypes.byref(desc), _ptr(Qc), _ptr(Kc), _ptr(Vc), Lc, kv_heads,
+                                     _ptr(block_list), block_size, max_blocks_per_row, _ptr(Oc), _ptr(lse), _stream()))
+
+
+def tsa_decompress(desc, Oc, idx, inv, k_keep, O=None, residual=None):
+    _check(load_library().tsa_decompress(ctypes.byref(desc), _ptr(Oc), _ptr(idx), _ptr(inv), k_keep,
+                                         _ptr(O), _ptr(residual), _stream()))
+
+
+def tsa_forward(desc, Q, K, V, k_keep, O, ws, residual=None, idx_out=None,
+                block_list=None, block_size=0, max_blocks_per_row=0):
+    p, n = _ws(ws)
+    _check(load_library().tsa_forward(ctypes.byref(desc), _ptr(Q), _ptr(K), _ptr(V), k_keep,
+                                      _ptr(block_list), block_size, max_blocks_per_row,
+                                      _ptr(O), _ptr(residual), _ptr(idx_out), p, n, _stream()))
+
+
+def alloc_workspace(desc, k_keep, device="cuda"):
+    """Device buffer of tsa_workspace_bytes() bytes (torch allocations are 256-byte aligned)."""
+    n = tsa_workspace_bytes(desc, k_keep)
+    if n == 0:
+        raise TsaError(TSA_ERR_ARG, tsa_last_error())
+    return torch.empty(n, dtype=torch.uint8, device=device)

@@ -1,0 +1,230 @@
+// C-ABI layer of libtsa: argument validation on the host, workspace carving, kernel launches.
+// Nothing here allocates device memory or synchronises with the host.
+#include "../../include/tsa.h"
+#include "tsa_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Checks the descriptor; on success fills the launcher's view of it.
+int check_desc(const tsa_desc* d, tsa::Dims* out) {
+  if (!d) return fail(TSA_ERR_ARG, "desc is NULL");
+  if (d->B < 1 || d->Hq < 1 || d->Hkv < 1 || d->L < 1) return fail(TSA_ERR_ARG, "B, Hq, Hkv, L must be >= 1");
+  if (d->Hq % d->Hkv != 0) return fail(TSA_ERR_ARG, "Hq (%d) is not a multiple of Hkv (%d)", d->Hq, d->Hkv);
+  if (d->d != 64 && d->d != 128) return fail(TSA_ERR_UNSUPPORTED, "head dimension %d: only 64 and 128 are built", d->d);
+  if (d->last_q < 1 || d->last_q > d->L || d->last_q > 128)
+    return fail(TSA_ERR_ARG, "last_q (%d) must lie in [1, min(L, 128)]", d->last_q);
+  if (d->pool_w != 1) return fail(TSA_ERR_UNSUPPORTED, "pool_w %d: only 1 (no pooling) is built", d->pool_w);
+  if (d->group_mode != 0 && d->group_mode != 1) return fail(TSA_ERR_ARG, "group_mode must be 0 or 1");
+  if (d->force_first < 0 || d->force_last < 0 || (long long)d->force_first + d->force_last > d->L)
+    return fail(TSA_ERR_ARG, "force_first / force_last out of range");
+  if (!(d->scale >= 0.0f) || !std::isfinite(d->scale)) return fail(TSA_ERR_ARG, "scale must be finite and >= 0");
+  if ((long long)d->B * d->Hq > 65535) return fail(TSA_ERR_UNSUPPORTED, "B*Hq > 65535");
+  out->B = d->B; out->Hq = d->Hq; out->Hkv = d->Hkv; out->L = d->L; out->d = d->d;
+  out->last_q = d->last_q; out->group_mode = d->group_mode;
+  out->force_first = d->force_first; out->force_last = d->force_last;
+  out->scale = d->scale > 0.0f ? d->scale : 1.0f / std::sqrt((float)d->d);
+  return TSA_OK;
+}
+
+int check_k(const tsa::Dims& dm, int32_t k_keep) {
+  if (k_keep < 1 || k_keep > dm.L) return fail(TSA_ERR_ARG, "k_keep (%d) must lie in [1, L=%d]", k_keep, dm.L);
+  return TSA_OK;
+}
+
+int check_ptr(const void* p, const char* name, bool optional = false) {
+  if (!p) return optional ? TSA_OK : fail(TSA_ERR_ARG, "%s is NULL", name);
+  if (misaligned(p)) return fail(TSA_ERR_ARG, "%s is not 16-byte aligned", name);
+  return TSA_OK;
+}
+
+int check_ws(const void* ws, size_t have, size_t need) {
+  if (need == 0) return TSA_OK;
+  if (!ws) return fail(TSA_ERR_WORKSPACE, "ws is NULL but %zu bytes are needed", need);
+  if (((uintptr_t)ws & 255u) != 0) return fail(TSA_ERR_WORKSPACE, "ws is not 256-byte aligned");
+  if (have < need) return fail(TSA_ERR_WORKSPACE, "workspace too small: %zu bytes given, %zu needed", have, need);
+  return TSA_OK;
+}
+
+int hip_status(hipError_t e, const char* what) {
+  if (e == hipSuccess) return TSA_OK;
+  return fail(TSA_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int check_block_list(const int32_t* bl, int32_t block_size, int32_t max_blocks) {
+  if (!bl) return TSA_OK;
+  if (block_size != 128) return fail(TSA_ERR_UNSUPPORTED, "block_size %d: only 128 is built", block_size);
+  if (max_blocks < 1) return fail(TSA_ERR_ARG, "max_blocks_per_row must be >= 1 with a block list");
+  if (((uintptr_t)bl & 3u) != 0) return fail(TSA_ERR_ARG, "block_list is not 4-byte aligned");
+  return TSA_OK;
+}
+
+// Carving of the workspace used by tsa_forward (every piece 256-byte aligned).
+struct ForwardWs {
+  size_t scores, score_ws, select_ws, idx, inv, Qc, Kc, Vc, Oc, total;
+};
+
+ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
+  ForwardWs w;
+  const size_t BHq = (size_t)dm.B * dm.Hq, BHkv = (size_t)dm.B * dm.Hkv;
+  const size_t Hs = dm.group_mode ? BHkv : BHq;
+  const size_t row = (size_t)dm.d * 2;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t at = off; off += align256(bytes); return at; };
+  w.scores = take(BHq * dm.L * sizeof(float));
+  w.score_ws = take(tsa::score_ws_bytes(dm));
+  w.select_ws = take(tsa::select_ws_bytes(dm));
+  w.idx = take(Hs * k * sizeof(int32_t));
+  w.inv = take(Hs * dm.L * sizeof(int32_t));
+  w.Qc = take(BHq * k * row);
+  w.Kc = take((dm.group_mode ? BHkv : BHq) * k * row);
+  w.Vc = take((dm.group_mode ? BHkv : BHq) * k * row);
+  w.Oc = take(BHq * k * row);
+  w.total = off;
+  return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tsa_version(void) { return 1; }
+
+const char* tsa_last_error(void) { return g_err; }
+
+int32_t tsa_keep_count(int32_t L, double tau) {
+  if (L < 1 || !(tau >= 0.0) || !(tau <= 1.0)) return 0;
+  const long long drop = (long long)std::floor(tau * (double)L);
+  long long keep = (long long)L - drop;
+  if (keep < 1) keep = 1;
+  if (keep > L) keep = L;
+  return (int32_t)keep;
+}
+
+size_t tsa_workspace_bytes(const tsa_desc* desc, int32_t k_keep) {
+  tsa::Dims dm;
+  if (check_desc(desc, &dm) != TSA_OK) return 0;
+  if (check_k(dm, k_keep) != TSA_OK) return 0;
+  return forward_layout(dm, k_keep).total;
+}
+
+int tsa_score(const tsa_desc* desc, const void* Q, const void* K, float* scores,
+              void* ws, size_t ws_bytes, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm))) return rc;
+  if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(scores, "scores"))) return rc;
+  if ((rc = check_ws(ws, ws_bytes, tsa::score_ws_bytes(dm)))) return rc;
+  return hip_status(tsa::launch_score(dm, Q, K, scores, ws, (hipStream_t)stream), "tsa_score");
+}
+
+int tsa_select(const tsa_desc* desc, const float* scores, int32_t k_keep,
+               int32_t* idx, int32_t* inv, void* ws, size_t ws_bytes, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep))) return rc;
+  if ((rc = check_ptr(scores, "scores")) || (rc = check_ptr(idx, "idx")) || (rc = check_ptr(inv, "inv", true))) return rc;
+  if ((rc = check_ws(ws, ws_bytes, tsa::select_ws_bytes(dm)))) return rc;
+  return hip_status(tsa::launch_select(dm, scores, k_keep, idx, inv, ws, (hipStream_t)stream), "tsa_select");
+}
+
+int tsa_compress(const tsa_desc* desc, const void* Q, const void* K, const void* V,
+                 const int32_t* idx, int32_t k_keep, void* Qc, void* Kc, void* Vc, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep))) return rc;
+  if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(V, "V")) || (rc = check_ptr(idx, "idx")) ||
+      (rc = check_ptr(Qc, "Qc")) || (rc = check_ptr(Kc, "Kc")) || (rc = check_ptr(Vc, "Vc")))
+    return rc;
+  return hip_status(tsa::launch_compress(dm, Q, K, V, idx, k_keep, Qc, Kc, Vc, (hipStream_t)stream), "tsa_compress");
+}
+
+int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void* Vc,
+               int32_t Lc, int32_t kv_heads,
+               const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
+               void* Oc, float* lse, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm))) return rc;
+  if (Lc < 1) return fail(TSA_ERR_ARG, "Lc (%d) must be >= 1", Lc);
+  if (kv_heads < 1 || dm.Hq % kv_heads != 0) return fail(TSA_ERR_ARG, "kv_heads (%d) must divide Hq (%d)", kv_heads, dm.Hq);
+  if ((rc = check_ptr(Qc, "Qc")) || (rc = check_ptr(Kc, "Kc")) || (rc = check_ptr(Vc, "Vc")) || (rc = check_ptr(Oc, "Oc")))
+    return rc;
+  if (lse && ((uintptr_t)lse & 3u)) return fail(TSA_ERR_ARG, "lse is not 4-byte aligned");
+  if ((rc = check_block_list(block_list, block_size, max_blocks_per_row))) return rc;
+  if ((long long)((dm.B * dm.Hq + 7) / 8) * 8 * ((Lc + 127) / 128) > 0x7fffffffLL)
+    return fail(TSA_ERR_UNSUPPORTED, "grid too large");
+  return hip_status(tsa::launch_attend(dm.B, dm.Hq, kv_heads, Lc, dm.d, dm.scale, Qc, Kc, Vc, block_list,
+                                       max_blocks_per_row, Oc, lse, (hipStream_t)stream), "tsa_attend");
+}
+
+int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, const int32_t* inv,
+                   int32_t k_keep, void* O, void* residual, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep))) return rc;
+  if ((rc = check_ptr(Oc, "Oc"))) return rc;
+  if (!O && !residual) return fail(TSA_ERR_ARG, "both O and residual are NULL");
+  if ((rc = check_ptr(O, "O", true)) || (rc = check_ptr(residual, "residual", true))) return rc;
+  if (O && (rc = check_ptr(inv, "inv"))) return rc;
+  if (residual && (rc = check_ptr(idx, "idx"))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  if (O && (rc = hip_status(tsa::launch_decompress(dm, Oc, inv, k_keep, O, st), "tsa_decompress"))) return rc;
+  if (residual && (rc = hip_status(tsa::launch_residual(dm, Oc, idx, k_keep, residual, st), "tsa_decompress(residual)"))) return rc;
+  return TSA_OK;
+}
+
+int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* V, int32_t k_keep,
+                const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
+                void* O, void* residual, int32_t* idx_out,
+                void* ws, size_t ws_bytes, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep))) return rc;
+  if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(V, "V"))) return rc;
+  if (!O && !residual) return fail(TSA_ERR_ARG, "both O and residual are NULL");
+  if ((rc = check_ptr(O, "O", true)) || (rc = check_ptr(residual, "residual", true)) || (rc = check_ptr(idx_out, "idx_out", true)))
+    return rc;
+  if ((rc = check_block_list(block_list, block_size, max_blocks_per_row))) return rc;
+  const ForwardWs w = forward_layout(dm, k_keep);
+  if ((rc = check_ws(ws, ws_bytes, w.total))) return rc;
+  char* base = (char*)ws;
+  float* scores = (float*)(base + w.scores);
+  int32_t* idx = (int32_t*)(base + w.idx);
+  int32_t* inv = (int32_t*)(base + w.inv);
+  void* Qc = base + w.Qc; void* Kc = base + w.Kc; void* Vc = base + w.Vc; void* Oc = base + w.Oc;
+  hipStream_t st = (hipStream_t)stream;
+  const int kvh = dm.group_mode ? dm.Hkv : dm.Hq;
+  if ((rc = hip_status(tsa::launch_score(dm, Q, K, scores, base + w.score_ws, st), "tsa_forward(score)"))) return rc;
+  if ((rc = hip_status(tsa::launch_select(dm, scores, k_keep, idx, inv, base + w.select_ws, st), "tsa_forward(select)"))) return rc;
+  if ((rc = hip_status(tsa::launch_compress(dm, Q, K, V, idx, k_keep, Qc, Kc, Vc, st), "tsa_forward(compress)"))) return rc;
+  if ((rc = hip_status(tsa::launch_attend(dm.B, dm.Hq, kvh, k_keep, dm.d, dm.scale, Qc, Kc, Vc, block_list,
+                                          max_blocks_per_row, Oc, nullptr, st), "tsa_forward(attend)"))) return rc;
+  if (O && (rc = hip_status(tsa::launch_decompress(dm, Oc, inv, k_keep, O, st), "tsa_forward(decompress)"))) return rc;
+  if (residual && (rc = hip_status(tsa::launch_residual(dm, Oc, idx, k_keep, residual, st), "tsa_forward(residual)"))) return rc;
+  if (idx_out) {
+    const size_t Hs = (size_t)dm.B * (dm.group_mode ? dm.Hkv : dm.Hq);
+    if ((rc = hip_status(hipMemcpyAsync(idx_out, idx, Hs * k_keep * sizeof(int32_t), hipMemcpyDeviceToDevice, st),
+                         "tsa_forward(idx copy)"))) return rc;
+  }
+  return TSA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,135 @@
+// Stage 1 compression (row gather of Q, K, V by S_h) and Stage 2 decompression (scatter of
+// the compressed output into a zero-filled full-length tensor, or into the residual stream).
+// Section 2.2 of the paper.  All three are pure data movement, bound by HBM bandwidth:
+// every lane moves 16 bytes, a row of d bf16 values is covered by d/8 adjacent lanes, so a
+// wavefront reads and writes whole rows as contiguous 128- or 256-byte segments.
+#include "tsa_internal.h"
+
+namespace tsa {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// One task = one compacted row (b, h, r): copy Q[b,h,S[r],:] -> Qc[b,h,r,:] and the K, V rows
+// of KV head h/g.  LPR lanes per row (d/8).
+template <int LPR>
+__global__ __launch_bounds__(kThreads) void compress_kernel(
+    const u32x4* __restrict__ Q, const u32x4* __restrict__ K, const u32x4* __restrict__ V,
+    const int32_t* __restrict__ idx, u32x4* __restrict__ Qc, u32x4* __restrict__ Kc, u32x4* __restrict__ Vc,
+    int Hq, int Hkv, int L, int k, int group_mode, long long n_tasks) {
+  const long long gtid = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const long long task = gtid / LPR;
+  const int lane = (int)(gtid % LPR);
+  if (task >= n_tasks) return;
+  const int r = (int)(task % k);
+  const long long bh = task / k;            // b * Hq + h
+  const int h = (int)(bh % Hq);
+  const long long b = bh / Hq;
+  const int g = Hq / Hkv;
+  const int kv = h / g;
+  const long long bkv = b * Hkv + kv;
+  const long long sel_head = group_mode ? bkv : bh;
+  const int t = idx[sel_head * k + r];
+  // LPR 16-byte units per row
+  Qc[(bh * k + r) * LPR + lane] = Q[(bh * L + t) * LPR + lane];
+  if (group_mode == 0) {
+    Kc[(bh * k + r) * LPR + lane] = K[(bkv * L + t) * LPR + lane];
+    Vc[(bh * k + r) * LPR + lane] = V[(bkv * L + t) * LPR + lane];
+  } else if (h % g == 0) {
+    Kc[(bkv * k + r) * LPR + lane] = K[(bkv * L + t) * LPR + lane];
+    Vc[(bkv * k + r) * LPR + lane] = V[(bkv * L + t) * LPR + lane];
+  }
+}
+
+// One task = one output row (b, h, t): O[b,h,t,:] = inv[t] >= 0 ? Oc[b,h,inv[t],:] : 0.
+template <int LPR>
+__global__ __launch_bounds__(kThreads) void decompress_kernel(
+    const u32x4* __restrict__ Oc, const int32_t* __restrict__ inv, u32x4* __restrict__ O,
+    int Hq, int g_sel, int L, int k, long long n_tasks) {
+  const long long gtid = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const long long task = gtid / LPR;
+  const int lane = (int)(gtid % LPR);
+  if (task >= n_tasks) return;
+  const int t = (int)(task % L);
+  const long long bh = task / L;
+  const long long sel_head = bh / g_sel;    // g_sel = 1 (per-head sets) or Hq/Hkv (per-group sets)
+  const int r = inv[sel_head * L + t];
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (r >= 0) v = Oc[(bh * k + r) * LPR + lane];
+  O[(bh * L + t) * LPR + lane] = v;
+}
+
+__device__ __forceinline__ uint32_t add_bf16_pair(uint32_t x, uint32_t o) {
+  // two bf16 in one dword: widen to fp32 (exact), add, round each sum to bf16 (nearest even)
+  const float x0 = __uint_as_float(x << 16), x1 = __uint_as_float(x & 0xffff0000u);
+  const float o0 = __uint_as_float(o << 16), o1 = __uint_as_float(o & 0xffff0000u);
+  bf16x2 s;
+  s[0] = (__bf16)(x0 + o0);
+  s[1] = (__bf16)(x1 + o1);
+  return __builtin_bit_cast(uint32_t, s);
+}
+
+// One task = one compacted row (b, h, r): residual[b, S[r], h*d:(h+1)*d] += Oc[b,h,r,:].
+template <int LPR>
+__global__ __launch_bounds__(kThreads) void residual_kernel(
+    const u32x4* __restrict__ Oc, const int32_t* __restrict__ idx, u32x4* __restrict__ X,
+    int Hq, int g_sel, int L, int k, long long n_tasks) {
+  const long long gtid = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const long long task = gtid / LPR;
+  const int lane = (int)(gtid % LPR);
+  if (task >= n_tasks) return;
+  const int r = (int)(task % k);
+  const long long bh = task / k;
+  const int h = (int)(bh % Hq);
+  const long long b = bh / Hq;
+  const int t = idx[(bh / g_sel) * k + r];
+  const u32x4 o = Oc[(bh * k + r) * LPR + lane];
+  u32x4* px = X + ((b * L + t) * Hq + h) * LPR + lane;
+  u32x4 x = *px;
+  x[0] = add_bf16_pair(x[0], o[0]);
+  x[1] = add_bf16_pair(x[1], o[1]);
+  x[2] = add_bf16_pair(x[2], o[2]);
+  x[3] = add_bf16_pair(x[3], o[3]);
+  *px = x;
+}
+
+inline unsigned blocks_for(long long n_tasks, int lpr) {
+  return (unsigned)((n_tasks * lpr + kThreads - 1) / kThreads);
+}
+
+}  // namespace
+
+hipError_t launch_compress(const Dims& dm, const void* Q, const void* K, const void* V, const int32_t* idx,
+                           int k_keep, void* Qc, void* Kc, void* Vc, hipStream_t st) {
+  const long long n = (long long)dm.B * dm.Hq * k_keep;
+  auto q = (const u32x4*)Q; auto k = (const u32x4*)K; auto v = (const u32x4*)V;
+  auto qc = (u32x4*)Qc; auto kc = (u32x4*)Kc; auto vc = (u32x4*)Vc;
+  if (dm.d == 128)
+    compress_kernel<16><<<blocks_for(n, 16), kThreads, 0, st>>>(q, k, v, idx, qc, kc, vc, dm.Hq, dm.Hkv, dm.L, k_keep, dm.group_mode, n);
+  else
+    compress_kernel<8><<<blocks_for(n, 8), kThreads, 0, st>>>(q, k, v, idx, qc, kc, vc, dm.Hq, dm.Hkv, dm.L, k_keep, dm.group_mode, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_decompress(const Dims& dm, const void* Oc, const int32_t* inv, int k_keep, void* O, hipStream_t st) {
+  const long long n = (long long)dm.B * dm.Hq * dm.L;
+  const int g_sel = dm.group_mode ? dm.Hq / dm.Hkv : 1;
+  if (dm.d == 128)
+    decompress_kernel<16><<<blocks_for(n, 16), kThreads, 0, st>>>((const u32x4*)Oc, inv, (u32x4*)O, dm.Hq, g_sel, dm.L, k_keep, n);
+  else
+    decompress_kernel<8><<<blocks_for(n, 8), kThreads, 0, st>>>((const u32x4*)Oc, inv, (u32x4*)O, dm.Hq, g_sel, dm.L, k_keep, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_residual(const Dims& dm, const void* Oc, const int32_t* idx, int k_keep, void* residual, hipStream_t st) {
+  const long long n = (long long)dm.B * dm.Hq * k_keep;
+  const int g_sel = dm.group_mode ? dm.Hq / dm.Hkv : 1;
+  if (dm.d == 128)
+    residual_kernel<16><<<blocks_for(n, 16), kThreads, 0, st>>>((const u32x4*)Oc, idx, (u32x4*)residual, dm.Hq, g_sel, dm.L, k_keep, n);
+  else
+    residual_kernel<8><<<blocks_for(n, 8), kThreads, 0, st>>>((const u32x4*)Oc, idx, (u32x4*)residual, dm.Hq, g_sel, dm.L, k_keep, n);
+  return hipGetLastError();
+}
+
+}  // namespace tsa

@@ -1,0 +1,62 @@
+// Internal declarations shared by the kernel files and the C-ABI layer of libtsa.
+// Device code here is written for gfx950 (CDNA4) only: 64-lane wavefronts, bf16 MFMA.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace tsa {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Register layout of v_mfma_f32_32x32x16_bf16 (one wavefront, lane l, lo = l % 32, hi = l / 32):
+//   A operand: 8 bf16 = A[row lo][k = 8*hi .. 8*hi+7]
+//   B operand: 8 bf16 = B[k = 8*hi .. 8*hi+7][col lo]
+//   C/D:       16 fp32, register r = D[row 8*(r/4) + 4*hi + (r%4)][col lo]
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ int c_row(int r, int hi) { return 8 * (r >> 2) + 4 * hi + (r & 3); }
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Shapes every launcher gets (validated by the C-ABI layer before any launch).
+struct Dims {
+  int B, Hq, Hkv, L, d, last_q, group_mode, force_first, force_last;
+  float scale;
+};
+
+// ---- launchers (each returns hipGetLastError() after queuing its kernels) ----
+
+// score.hip
+size_t score_ws_bytes(const Dims& dm);
+hipError_t launch_score(const Dims& dm, const void* Q, const void* K, float* scores, void* ws, hipStream_t st);
+
+// select.hip
+size_t select_ws_bytes(const Dims& dm);
+hipError_t launch_select(const Dims& dm, const float* scores, int k_keep, int32_t* idx, int32_t* inv,
+                         void* ws, hipStream_t st);
+
+// gather_scatter.hip
+hipError_t launch_compress(const Dims& dm, const void* Q, const void* K, const void* V, const int32_t* idx,
+                           int k_keep, void* Qc, void* Kc, void* Vc, hipStream_t st);
+hipError_t launch_decompress(const Dims& dm, const void* Oc, const int32_t* inv, int k_keep, void* O, hipStream_t st);
+hipError_t launch_residual(const Dims& dm, const void* Oc, const int32_t* idx, int k_keep, void* residual, hipStream_t st);
+
+// attend.hip
+hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
+                         const void* Vc, const int32_t* block_list, int max_blocks_per_row, void* Oc, float* lse,
+                         hipStream_t st);
+
+}  // namespace tsa

@@ -1,0 +1,76 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and validates arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from oracle import tsa_oracle as orc
+from paper_2602_03216_amd import binding as tsa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return tsa.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "tsa.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(tsa_[a-z_]+)\s*\(", header))
+    assert declared == set(tsa.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_desc_struct_matches_header(lib):
+    assert ctypes.sizeof(tsa.tsa_desc) == 44
+    assert lib.tsa_version() == 1
+
+
+def test_keep_count_matches_oracle_rule(lib):
+    for L in (1, 2, 10, 1024, 8192, 32768, 65536, 131072, 100003):
+        for tau in (0.0, 0.3, 0.5, 0.75, 0.9, 0.999, 1.0):
+            assert tsa.tsa_keep_count(L, tau) == orc.keep_count(L, tau)
+    assert tsa.tsa_keep_count(0, 0.5) == 0 and tsa.tsa_keep_count(10, 1.5) == 0 and tsa.tsa_keep_count(10, -0.1) == 0
+
+
+def test_workspace_bytes(lib):
+    d = tsa.make_desc(1, 32, 8, 131072, 128)
+    n = tsa.tsa_workspace_bytes(d, 32768)
+    # at least the scores, the two index maps and four compacted tensors
+    assert n >= 32 * 131072 * 4 * 2 + 32 * 32768 * 4 + 4 * 32 * 32768 * 128 * 2
+    assert tsa.tsa_workspace_bytes(d, 0) == 0 and tsa.tsa_workspace_bytes(d, 131073) == 0
+    assert tsa.tsa_workspace_bytes(tsa.make_desc(1, 32, 7, 1024, 128), 16) == 0
+    assert "multiple" in tsa.tsa_last_error()
+    assert tsa.tsa_workspace_bytes(tsa.make_desc(1, 4, 4, 1024, 96), 16) == 0
+    assert tsa.tsa_workspace_bytes(tsa.make_desc(1, 4, 4, 32, 64, last_q=64), 16) == 0
+    g1 = tsa.tsa_workspace_bytes(tsa.make_desc(1, 32, 8, 4096, 128, group_mode=1), 1024)
+    g0 = tsa.tsa_workspace_bytes(tsa.make_desc(1, 32, 8, 4096, 128, group_mode=0), 1024)
+    assert 0 < g1 < g0
+
+
+def test_entry_points_reject_bad_arguments_before_any_launch(lib):
+    d = tsa.make_desc(1, 4, 4, 1024, 64)
+    dp = ctypes.byref(d)
+    fake = ctypes.c_void_p(0x1000)       # aligned, never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x1004)
+    assert lib.tsa_score(dp, None, fake, fake, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_score(dp, odd, fake, fake, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_score(dp, fake, fake, fake, None, 0, None) == tsa.TSA_ERR_WORKSPACE
+    assert lib.tsa_score(dp, fake, fake, fake, fake, 16, None) == tsa.TSA_ERR_WORKSPACE
+    assert lib.tsa_select(dp, fake, 0, fake, fake, None, 0, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_select(dp, fake, 1025, fake, fake, None, 0, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_compress(dp, fake, fake, fake, None, 16, fake, fake, fake, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_attend(dp, fake, fake, fake, 0, 4, None, 0, 0, fake, None, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_attend(dp, fake, fake, fake, 16, 3, None, 0, 0, fake, None, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_attend(dp, fake, fake, fake, 256, 4, fake, 64, 3, fake, None, None) == tsa.TSA_ERR_UNSUPPORTED
+    assert lib.tsa_decompress(dp, fake, fake, fake, 16, None, None, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_forward(dp, fake, fake, fake, 16, None, 0, 0, fake, None, None, fake, 64, None) == tsa.TSA_ERR_WORKSPACE
+    assert "workspace" in tsa.tsa_last_error()
+    bad = tsa.make_desc(1, 4, 4, 1024, 64, pool_w=3)
+    assert lib.tsa_score(ctypes.byref(bad), fake, fake, fake, fake, 1 << 30, None) == tsa.TSA_ERR_UNSUPPORTED
+    assert lib.tsa_score(None, fake, fake, fake, fake, 1 << 30, None) == tsa.TSA_ERR_ARG

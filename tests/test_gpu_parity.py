@@ -1,0 +1,250 @@
+"""GPU parity, entry point by entry point, through the C ABI: every tsa_* call against the CPU
+oracle on seeded inputs, at sizes the oracle finishes quickly that still span several tiles
+and a ragged tail, plus the edge cases of each step.  Index and byte work is compared
+bit-exactly; floating point within the tolerances in tests/gpu_util.py."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tsa_oracle as orc
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tsa():
+    from paper_2602_03216_amd import binding
+    binding.load_library(build_if_missing=False)
+    return binding
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def _ws(tsa, desc, k):
+    return tsa.alloc_workspace(desc, k, gu.DEV)
+
+
+# ------------------------------------------------------------------ score
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,d,Lq", [
+    (1, 4, 4, 1024, 64, 64),      # workload 1 shape
+    (2, 4, 2, 1500, 128, 64),     # batch, grouped KV heads, ragged length
+    (1, 3, 1, 2077, 128, 17),     # odd group size, window not a multiple of the tile
+    (1, 2, 2, 100, 64, 100),      # window = whole sequence
+    (1, 2, 1, 33, 128, 1),        # single query
+    (1, 2, 2, 5000, 128, 128),    # widest window
+    (1, 7, 1, 1030, 128, 64),     # last chunk holds only window keys
+])
+def test_score(tsa, B, Hq, Hkv, L, d, Lq):
+    r = _rng(100 + L)
+    Qb, Kb = gu.rand_bits(r, (B, Hq, L, d)), gu.rand_bits(r, (B, Hkv, L, d), 1.3)
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq)
+    s = torch.full((B, Hq, L), -1.0, dtype=torch.float32, device=gu.DEV)
+    tsa.tsa_score(desc, gu.to_dev(Qb), gu.to_dev(Kb), s, _ws(tsa, desc, 1))
+    torch.cuda.synchronize()
+    want = orc.score(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), Lq)
+    gu.assert_scores_close(s.cpu().numpy(), want, "score")
+    assert np.allclose(s.sum(-1).cpu().numpy(), Lq, rtol=1e-4)
+
+
+def test_score_custom_scale_and_determinism(tsa):
+    r = _rng(7)
+    B, Hq, Hkv, L, d, Lq = 1, 4, 2, 3000, 128, 64
+    Qb, Kb = gu.rand_bits(r, (B, Hq, L, d)), gu.rand_bits(r, (B, Hkv, L, d))
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq, scale=0.05)
+    Q, K = gu.to_dev(Qb), gu.to_dev(Kb)
+    ws = _ws(tsa, desc, 1)
+    s1 = torch.empty((B, Hq, L), dtype=torch.float32, device=gu.DEV)
+    s2 = torch.empty_like(s1)
+    tsa.tsa_score(desc, Q, K, s1, ws)
+    tsa.tsa_score(desc, Q, K, s2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(s1, s2)
+    gu.assert_scores_close(s1.cpu().numpy(), orc.score(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), Lq, scale=0.05))
+
+
+# ------------------------------------------------------------------ select
+
+def _run_select(tsa, scores_np, k, **kw):
+    B, Hq, L = scores_np.shape
+    Hkv = kw.pop("Hkv", Hq)
+    desc = tsa.make_desc(B, Hq, Hkv, L, 128, min(64, L), **kw)
+    Hs = Hkv if desc.group_mode else Hq
+    s = torch.from_numpy(scores_np.astype(np.float32)).to(gu.DEV)
+    idx = torch.full((B, Hs, k), -7, dtype=torch.int32, device=gu.DEV)
+    inv = torch.full((B, Hs, L), -7, dtype=torch.int32, device=gu.DEV)
+    tsa.tsa_select(desc, s, k, idx, inv, _ws(tsa, desc, k))
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), inv.cpu().numpy()
+
+
+@pytest.mark.parametrize("L,k", [(5, 2), (64, 1), (64, 64), (1000, 250), (1025, 1), (4097, 4097),
+                                 (16384, 4096), (33000, 3300), (70001, 17500)])
+def test_select_random_scores(tsa, L, k):
+    s = _rng(200 + L).random((2, 3, L)).astype(np.float32)
+    idx, inv = _run_select(tsa, s, k)
+    widx, winv = orc.select(s, k)
+    assert np.array_equal(idx, widx) and np.array_equal(inv, winv)
+
+
+def test_select_exact_ties(tsa):
+    idx, inv = _run_select(tsa, np.array([[[3.0, 1.0, 3.0, 3.0, 0.0]]]), 2)
+    assert idx[0, 0].tolist() == [0, 2] and inv[0, 0].tolist() == [0, -1, 1, -1, -1]
+    r = _rng(3)
+    for L, k, levels in ((3000, 700, 4), (5000, 4999, 2), (2048, 1024, 1), (9000, 10, 3)):
+        s = r.integers(0, levels, size=(1, 4, L)).astype(np.float32) * 0.25      # few distinct values, many ties
+        idx, inv = _run_select(tsa, s, k)
+        widx, winv = orc.select(s, k)
+        assert np.array_equal(idx, widx) and np.array_equal(inv, winv)
+    # signed zeros compare equal, negative scores order correctly
+    s = np.array([[[-0.0, 0.0, -1.0, 0.0, -2.0, 5.0]]], dtype=np.float32)
+    idx, _ = _run_select(tsa, s, 3)
+    assert idx[0, 0].tolist() == [0, 1, 5]
+    idx, _ = _run_select(tsa, s, 5)
+    assert idx[0, 0].tolist() == [0, 1, 2, 3, 5]
+
+
+def test_select_forced_tokens_and_group_mode(tsa):
+    s = _rng(5).random((1, 8, 3000)).astype(np.float32)
+    idx, inv = _run_select(tsa, s, 300, force_first=4, force_last=7)
+    widx, winv = orc.select(s, 300, 4, 7)
+    assert np.array_equal(idx, widx) and np.array_equal(inv, winv)
+    # group mode: the sets are chosen from fp32 group sums; quantise so that the sums are exact
+    sq = np.round(s * 4096) / 4096
+    idx, inv = _run_select(tsa, sq, 500, Hkv=2, group_mode=1)
+    widx, winv = orc.select(orc.group_scores(sq.astype(np.float64), 4), 500)
+    assert idx.shape == (1, 2, 500)
+    assert np.array_equal(idx, widx) and np.array_equal(inv, winv)
+
+
+# ------------------------------------------------------------------ compress / decompress
+
+@pytest.mark.parametrize("d,group_mode", [(128, 0), (64, 0), (128, 1)])
+def test_compress_decompress_bit_exact(tsa, d, group_mode):
+    r = _rng(300 + d + group_mode)
+    B, Hq, Hkv, L, k = 2, 6, 2, 777, 201
+    Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, L, d)), gu.rand_bits(r, (B, Hkv, L, d)), gu.rand_bits(r, (B, Hkv, L, d))
+    Hs = Hkv if group_mode else Hq
+    idx_np = np.stack([np.stack([np.sort(r.choice(L, k, replace=False)) for _ in range(Hs)]) for _ in range(B)]).astype(np.int32)
+    inv_np = np.full((B, Hs, L), -1, dtype=np.int32)
+    for b in range(B):
+        for h in range(Hs):
+            inv_np[b, h, idx_np[b, h]] = np.arange(k)
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, 64, group_mode=group_mode)
+    idx, inv = torch.from_numpy(idx_np).to(gu.DEV), torch.from_numpy(inv_np).to(gu.DEV)
+    Hk = Hkv if group_mode else Hq
+    Qc = torch.zeros((B, Hq, k, d), dtype=torch.bfloat16, device=gu.DEV)
+    Kc = torch.zeros((B, Hk, k, d), dtype=torch.bfloat16, device=gu.DEV)
+    Vc = torch.zeros_like(Kc)
+    tsa.tsa_compress(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), idx, k, Qc, Kc, Vc)
+    wq, wk, wv = orc.compress(Qb, Kb, Vb, idx_np, group_mode)
+    assert np.array_equal(gu.from_dev(Qc), wq) and np.array_equal(gu.from_dev(Kc), wk) and np.array_equal(gu.from_dev(Vc), wv)
+    # decompress: every element written (start from garbage), unselected rows exactly zero
+    O = torch.full((B, Hq, L, d), 7.0, dtype=torch.bfloat16, device=gu.DEV)
+    tsa.tsa_decompress(desc, Qc, idx, inv, k, O=O)
+    assert np.array_equal(gu.from_dev(O), orc.decompress(wq, idx_np, L))
+    # residual mode
+    xb = gu.rand_bits(r, (B, L, Hq * d))
+    x = gu.to_dev(xb)
+    tsa.tsa_decompress(desc, Qc, idx, inv, k, residual=x)
+    want = orc.residual_add(xb, wq, idx_np)
+    got = gu.from_dev(x)
+    diff = np.abs(orc.bf16_to_f64(got) - orc.bf16_to_f64(want))
+    assert (got != want).mean() < 1e-4 and diff.max() <= 2.0 ** -6        # fp32 add vs exact add: at most one ulp, rarely
+    untouched = np.ones((B, L, Hq), dtype=bool)
+    for b in range(B):
+        for h in range(Hq):
+            untouched[b, idx_np[b, h // (Hq // Hs)], h] = False
+    assert np.array_equal(got.reshape(B, L, Hq, d)[untouched], xb.reshape(B, L, Hq, d)[untouched])
+
+
+def test_compress_keep_all_is_identity(tsa):
+    r = _rng(11)
+    B, H, L, d = 1, 2, 130, 128
+    Qb = gu.rand_bits(r, (B, H, L, d))
+    idx = torch.arange(L, dtype=torch.int32, device=gu.DEV).repeat(B, H, 1).contiguous()
+    desc = tsa.make_desc(B, H, H, L, d, 64)
+    Qc, Kc, Vc = (torch.zeros((B, H, L, d), dtype=torch.bfloat16, device=gu.DEV) for _ in range(3))
+    Q = gu.to_dev(Qb)
+    tsa.tsa_compress(desc, Q, Q, Q, idx, L, Qc, Kc, Vc)
+    assert torch.equal(Qc, Q) and torch.equal(Kc, Q) and torch.equal(Vc, Q)
+
+
+# ------------------------------------------------------------------ attend
+
+@pytest.mark.parametrize("B,Hq,Hk,Lc,d", [
+    (1, 2, 2, 1, 128), (1, 2, 2, 63, 128), (1, 2, 1, 64, 128), (1, 4, 2, 65, 64), (2, 2, 2, 128, 128),
+    (1, 3, 3, 129, 128), (1, 8, 2, 300, 128), (1, 4, 4, 256, 64), (1, 9, 3, 1000, 128), (1, 2, 2, 2049, 64),
+])
+def test_attend_matches_oracle(tsa, B, Hq, Hk, Lc, d):
+    r = _rng(400 + Lc + d)
+    Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d))
+    desc = tsa.make_desc(B, Hq, Hk, max(Lc, 1), d, 1)
+    O = torch.full((B, Hq, Lc, d), 9.0, dtype=torch.bfloat16, device=gu.DEV)
+    lse = torch.zeros((B, Hq, Lc), dtype=torch.float32, device=gu.DEV)
+    tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, Hk, O, lse)
+    torch.cuda.synchronize()
+    want, wlse = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), return_lse=True)
+    gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend")
+    assert np.abs(lse.cpu().numpy() - wlse).max() < 2e-3
+    # row 0 attends to a single key: the output is v_0 exactly
+    g = Hq // Hk
+    for h in range(Hq):
+        assert np.array_equal(gu.from_dev(O)[0, h, 0], Vb[0, h // g, 0])
+
+
+def test_attend_large_logits_and_scale(tsa):
+    r = _rng(21)
+    B, H, Lc, d = 1, 2, 500, 128
+    Qb, Kb, Vb = gu.rand_bits(r, (B, H, Lc, d), 4.0), gu.rand_bits(r, (B, H, Lc, d), 4.0), gu.rand_bits(r, (B, H, Lc, d))
+    desc = tsa.make_desc(B, H, H, Lc, d, 1, scale=0.2)        # logits of several hundred: the running max must hold
+    O = torch.empty((B, H, Lc, d), dtype=torch.bfloat16, device=gu.DEV)
+    tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, H, O)
+    want = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), scale=0.2)
+    gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(large logits)")
+
+
+@pytest.mark.parametrize("Lc,window", [(1000, 256), (1300, 128), (640, 4096)])
+def test_attend_block_list(tsa, Lc, window):
+    r = _rng(500 + Lc)
+    B, Hq, Hk, d, Bs = 1, 4, 2, 128, 128
+    Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d))
+    bl = orc.lambda_block_list(Lc, Bs, window, 1)
+    desc = tsa.make_desc(B, Hq, Hk, Lc, d, 1)
+    O = torch.empty((B, Hq, Lc, d), dtype=torch.bfloat16, device=gu.DEV)
+    tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, Hk, O,
+                   block_list=torch.from_numpy(bl).to(gu.DEV), block_size=Bs, max_blocks_per_row=bl.shape[1])
+    want = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), block_list=bl, block_size=Bs)
+    gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(block list)")
+
+
+# ------------------------------------------------------------------ forward
+
+@pytest.mark.parametrize("Hq,Hkv,L,d,Lq,k,group_mode,plant", [
+    (4, 2, 1111, 128, 64, 300, 0, "direction"),
+    (4, 4, 700, 64, 32, 699, 0, "norm"),
+    (6, 2, 900, 128, 64, 129, 1, "zipf_sink"),
+    (2, 2, 257, 128, 64, 257, 0, "direction"),     # keep everything: dense causal attention
+    (2, 1, 200, 64, 8, 1, 0, "norm"),              # keep a single token
+])
+def test_forward_small(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant):
+    from paper_2602_03216_amd import inputs as gen
+    from tests.margin import enforce_margin
+    cfg = dict(id=90, name="small", B=1, Hq=Hq, Hkv=Hkv, L=L, d=d, last_q=Lq, plant=plant, n_plant=20, norm_factor=3.0,
+               frac_plant=0.1, boost=4.0, sink_boost=6.0, n_sink=4, zipf_a=1.2)
+    inp = gen.make_inputs(cfg, seed=600 + L)
+    enforce_margin(inp, [k], group_mode)            # the k-th / (k+1)-th scores are separated: one right answer
+    desc = tsa.make_desc(1, Hq, Hkv, L, d, Lq, group_mode=group_mode)
+    Hs = Hkv if group_mode else Hq
+    O = torch.full((1, Hq, L, d), 3.0, dtype=torch.bfloat16, device=gu.DEV)
+    idx = torch.zeros((1, Hs, k), dtype=torch.int32, device=gu.DEV)
+    tsa.tsa_forward(desc, gu.to_dev(inp.Q), gu.to_dev(inp.K), gu.to_dev(inp.V), k, O, _ws(tsa, desc, k), idx_out=idx)
+    torch.cuda.synchronize()
+    ref = orc.forward(inp.Q, inp.K, inp.V, k, Lq, group_mode=group_mode)
+    assert np.array_equal(idx.cpu().numpy(), ref["idx"])
+    gu.assert_output_close(gu.from_dev(O), ref["O"], "forward")
+    sel = ref["inv"] >= 0
+    assert not gu.from_dev(O)[np.repeat(~sel, Hq // Hs, axis=1)].any()
