@@ -1,0 +1,231 @@
+"""Benchmark of the Token Sparse Attention prefill hot path on one MI355X.
+
+A step is one pass of the whole path (tsa_forward: score -> select -> compress -> attend ->
+decompress) over one layer's Q, K, V, which are resident in HBM before the timed region.
+The headline workload is the 128K-token grouped-KV layer at sparsity tau = 0.75; the JSON line
+also carries the per-step breakdown, the other tau of the sweep, the 32K workload, the library's
+own dense attention at the same shapes (speedup denominator), the roofline of the dominant
+kernel (attend, bf16 MFMA) and the CPU oracle timed on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--quick]
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+HBM_PEAK_GBS = 8000.0               # MI355X HBM3E
+
+
+def _events_ms(fn, iters, torch):
+    """Average duration of fn() in ms over `iters` launches, HIP events on the current stream
+    (the stream every tsa_* call is queued on)."""
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def algorithmic_work(cfg, k):
+    """Bytes / flops the method itself has to move or compute, per layer (B = 1)."""
+    Hq, Hkv, L, d, Lq = cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"]
+    e = 2
+    return {
+        "score_bytes": Hkv * L * d * e + Hq * Lq * d * e + Hq * L * 4,
+        "score_flops": 2 * (2 * Hq * Lq * L * d),
+        "select_bytes": Hq * L * 4 + Hq * k * 4 + Hq * L * 4,
+        "compress_bytes": 6 * Hq * k * d * e + Hq * k * 4,
+        "attend_flops": 2 * Hq * k * (k + 1) * d,
+        "decompress_bytes": Hq * L * d * e + Hq * k * d * e + Hq * L * 4,
+        "dense_flops": 2 * Hq * L * (L + 1) * d,
+    }
+
+
+def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, part_iters):
+    import numpy as np
+    inp = gen.make_inputs(cfg_id)
+    cfg = inp.cfg
+    dev = "cuda:0"
+    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    Q, K, V = to_dev(inp.Q), to_dev(inp.K), to_dev(inp.V)
+    B, Hq, Hkv, L, d, Lq = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"]
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq)
+    O = torch.empty((B, Hq, L, d), dtype=torch.bfloat16, device=dev)
+    out = {"workload": cfg["name"], "L": L, "Hq": Hq, "Hkv": Hkv, "d": d, "last_q": Lq, "per_tau": {}}
+
+    # own dense attention at the same shape: the same attend kernel on the uncompressed tensors
+    dense = lambda: tsa.tsa_attend(desc, Q, K, V, L, Hkv, O)
+    dense()
+    torch.cuda.synchronize()
+    t_dense = _events_ms(dense, dense_iters, torch)
+    w_dense = algorithmic_work(cfg, L)
+    out["dense_ms"] = t_dense
+    out["dense_tflops"] = w_dense["dense_flops"] / t_dense / 1e9
+    out["dense_frac_mfma_peak"] = out["dense_tflops"] / MFMA_BF16_PEAK_TFLOPS
+
+    for tau in taus:
+        k = tsa.tsa_keep_count(L, tau)
+        ws = tsa.alloc_workspace(desc, k, dev)
+        fwd = lambda: tsa.tsa_forward(desc, Q, K, V, k, O, ws)
+        for _ in range(warmup):
+            fwd()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        t_fwd = _events_ms(fwd, steps, torch)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        # the five entry points one by one, on buffers of their own
+        scores = torch.empty((B, Hq, L), dtype=torch.float32, device=dev)
+        idx = torch.empty((B, Hq, k), dtype=torch.int32, device=dev)
+        inv = torch.empty((B, Hq, L), dtype=torch.int32, device=dev)
+        Qc = torch.empty((B, Hq, k, d), dtype=torch.bfloat16, device=dev)
+        Kc, Vc, Oc = torch.empty_like(Qc), torch.empty_like(Qc), torch.empty_like(Qc)
+        parts = {
+            "score": lambda: tsa.tsa_score(desc, Q, K, scores, ws),
+            "select": lambda: tsa.tsa_select(desc, scores, k, idx, inv, ws),
+            "compress": lambda: tsa.tsa_compress(desc, Q, K, V, idx, k, Qc, Kc, Vc),
+            "attend": lambda: tsa.tsa_attend(desc, Qc, Kc, Vc, k, Hq, Oc),
+            "decompress": lambda: tsa.tsa_decompress(desc, Oc, idx, inv, k, O=O),
+        }
+        t = {}
+        for name, fn in parts.items():
+            fn()
+            torch.cuda.synchronize()
+            t[name] = _events_ms(fn, part_iters, torch)
+        w = algorithmic_work(cfg, k)
+        rec = {
+            "k_keep": k, "forward_ms": t_fwd, "forward_wall_ms": wall,
+            "score_ms": t["score"], "select_ms": t["select"], "compress_ms": t["compress"],
+            "attend_ms": t["attend"], "decompress_ms": t["decompress"],
+            "speedup_attend_vs_dense": t_dense / t["attend"],
+            "speedup_layer_vs_dense": t_dense / t_fwd,
+            "ideal_attend_speedup": (L / k) ** 2,
+            "attend_tflops": w["attend_flops"] / t["attend"] / 1e9,
+            "attend_frac_mfma_peak": w["attend_flops"] / t["attend"] / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+            "score_gbs": w["score_bytes"] / t["score"] / 1e6,
+            "score_tflops": w["score_flops"] / t["score"] / 1e9,
+            "select_gbs": w["select_bytes"] / t["select"] / 1e6,
+            "compress_gbs": w["compress_bytes"] / t["compress"] / 1e6,
+            "decompress_gbs": w["decompress_bytes"] / t["decompress"] / 1e6,
+            "overhead_frac_of_forward": (t["score"] + t["select"] + t["compress"] + t["decompress"]) / t_fwd,
+        }
+        for nm in ("score", "select", "compress", "decompress"):
+            rec[nm + "_frac_hbm_peak"] = rec[nm + "_gbs"] / HBM_PEAK_GBS
+        out["per_tau"][str(tau)] = rec
+        del ws, scores, idx, inv, Qc, Kc, Vc, Oc
+    return out, inp
+
+
+def cpu_baseline(inp, k, budget_rows=256):
+    """The CPU oracle, as it stands, on a bounded sample of the headline workload: scoring and
+    selection in full; compression, attention and decompression for a few heads / rows, scaled
+    to the whole layer (the scaling is by rows x keys actually computed)."""
+    import numpy as np
+    from oracle import tsa_oracle as orc
+    cfg = inp.cfg
+    Hq, Hkv, L, d, Lq = cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"]
+    g = Hq // Hkv
+    t0 = time.perf_counter()
+    s = orc.score(orc.bf16_to_f64(inp.Q[:, :, L - Lq:, :]), orc.bf16_to_f64(inp.K), Lq)
+    t_score = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    idx, inv = orc.select(s, k)
+    t_select = time.perf_counter() - t0
+    # attention on sampled compacted rows of two heads; cost model: time per (row, visible key) pair
+    heads = sorted({0, Hq // 3, (2 * Hq) // 3, Hq - 1})
+    rows = np.unique(np.linspace(0, k - 1, budget_rows).astype(np.int64))
+    t_gather = t_att = 0.0
+    pairs = 0
+    for h in heads:
+        t0 = time.perf_counter()
+        toks = idx[0, h]
+        Qh = orc.bf16_to_f64(inp.Q[0, h, toks])[None, None]
+        Kh = orc.bf16_to_f64(inp.K[0, h // g, toks])[None, None]
+        Vh = orc.bf16_to_f64(inp.V[0, h // g, toks])[None, None]
+        t_gather += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        orc.f64_to_bf16(orc.attend(Qh, Kh, Vh, rows=rows))
+        t_att += time.perf_counter() - t0
+        pairs += len(rows) * k            # the oracle forms every column of a sampled row, masked or not
+    t_attend_full = t_att / pairs * (Hq * k * k)
+    t_gather_full = t_gather / len(heads) * Hq
+    t0 = time.perf_counter()
+    Oc = np.zeros((1, 2, k, d), dtype=np.uint16)
+    orc.decompress(Oc, idx[:, :2], L)
+    t_dec_full = (time.perf_counter() - t0) / 2 * Hq
+    total = t_score + t_select + t_gather_full + t_attend_full + t_dec_full
+    return {
+        "value": total * 1e3, "unit": "ms/layer (extrapolated)", "cores": os.cpu_count(), "kind": "oracle",
+        "sample": "score+select of all %d heads in full (%.1f s + %.1f s measured); gather, attend, scatter on %d heads x %d "
+                  "sampled compacted rows (%.1f s measured), scaled to %d heads x %d rows by (row, key) pairs"
+                  % (Hq, t_score, t_select, len(heads), len(rows), t_gather + t_att, Hq, k),
+        "measured_s": t_score + t_select + t_gather + t_att,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quick", action="store_true", help="headline workload and tau only")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (heads shard trivially across GPUs, no collective is "
+              "part of the path); run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2602_03216_amd import binding as tsa, inputs as gen
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    tsa.load_library(build_if_missing=True)
+    torch.cuda.set_device(0)
+
+    head_tau = 0.75
+    taus128 = (0.75,) if args.quick else gen.CONFIGS[4]["taus"]
+    r128, inp128 = bench_workload(tsa, torch, gen, 4, taus128, args.steps, args.warmup, dense_iters=3, part_iters=5)
+    detail = {"gqa_128k": r128}
+    if not args.quick:
+        r32, _ = bench_workload(tsa, torch, gen, 3, gen.CONFIGS[3]["taus"], args.steps, args.warmup, dense_iters=5, part_iters=10)
+        detail["gqa_32k"] = r32
+    head = r128["per_tau"][str(head_tau)]
+    cfg = inp128.cfg
+    w = algorithmic_work(cfg, head["k_keep"])
+    line = {
+        "metric": "prefill_attention_ms_per_layer", "value": head["forward_ms"], "unit": "ms",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["forward_ms"],
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "gqa_128k: B=1, 32 query heads / 8 KV heads, d=128, L=131072, tau=0.75 (k_keep=%d), "
+                               "last_q=64, per-query-head sets, tsa_forward" % head["k_keep"],
+                   "tau": head_tau, "k_keep": head["k_keep"]},
+        "speedup_vs_own_dense": head["speedup_layer_vs_dense"],
+        "speedup_attend_vs_own_dense": head["speedup_attend_vs_dense"],
+        "ideal_attend_speedup": head["ideal_attend_speedup"],
+        "dense_ms": r128["dense_ms"],
+        "roofline": {"kernel": "attend_kernel<128>", "bound": "mfma", "achieved": head["attend_tflops"],
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": head["attend_frac_mfma_peak"],
+                     "flops_per_launch": w["attend_flops"], "avg_launch_ms": head["attend_ms"], "traffic": None},
+        "paper_context": "paper reports up to x3.23 attention speedup at 128K on one NVIDIA A100 80GB (other hardware; not a target)",
+        "detail": detail,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(inp128, head["k_keep"])
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

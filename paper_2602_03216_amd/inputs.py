@@ -14,8 +14,12 @@ All tensors are returned as numpy uint16 arrays holding bf16 bit patterns.
 from __future__ import annotations
 
 import math
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 import numpy as np
+
+_N_THREADS = max(1, min(16, os.cpu_count() or 1))
 
 SEED_BASE = 260203216
 
@@ -61,12 +65,31 @@ class Inputs:
     extra: dict = field(default_factory=dict)
 
 
-def _normal_bf16(rng: np.random.Generator, shape) -> np.ndarray:
-    """N(0,1) in float32, generated head by head to bound peak memory."""
+def _normal_f32(seed: int, tensor_id: int, shape) -> np.ndarray:
+    """N(0,1) in float32.  Every (tensor, head) slice has its own PCG64 stream seeded from
+    (seed, tensor_id, head index), so slices can be drawn by a few threads in parallel and the
+    result does not depend on the number of threads."""
     out = np.empty(shape, dtype=np.float32)
     flat = out.reshape(-1, shape[-2], shape[-1])
-    for i in range(flat.shape[0]):
-        flat[i] = rng.standard_normal(flat.shape[1:], dtype=np.float32)
+
+    def fill(i):
+        rng = np.random.Generator(np.random.PCG64([seed, tensor_id, i]))
+        rng.standard_normal(flat.shape[1:], dtype=np.float32, out=flat[i])
+
+    with ThreadPoolExecutor(max_workers=_N_THREADS) as pool:
+        list(pool.map(fill, range(flat.shape[0])))
+    return out
+
+
+def _to_bf16_parallel(x: np.ndarray) -> np.ndarray:
+    out = np.empty(x.shape, dtype=np.uint16)
+    xf, of = x.reshape(-1, x.shape[-2], x.shape[-1]), out.reshape(-1, x.shape[-2], x.shape[-1])
+
+    def conv(i):
+        of[i] = f32_to_bf16_bits(xf[i])
+
+    with ThreadPoolExecutor(max_workers=_N_THREADS) as pool:
+        list(pool.map(conv, range(xf.shape[0])))
     return out
 
 
@@ -103,9 +126,9 @@ def make_inputs(cfg_id: int | dict, seed: int | None = None, layer: int = 0,
     cfg["last_q"] = Lq
     assert B == 1, "the recipes below are written for B = 1 (every workload of the paper's setup)"
 
-    Q = _normal_bf16(rng, (B, Hq, Ln, d))
-    K = _normal_bf16(rng, (B, Hkv, Ln, d))
-    V = _normal_bf16(rng, (B, Hkv, Ln, d))
+    Q = _normal_f32(seed, 1, (B, Hq, Ln, d))
+    K = _normal_f32(seed, 2, (B, Hkv, Ln, d))
+    V = _normal_f32(seed, 3, (B, Hkv, Ln, d))
     planted: list = []
     directions = None
     key_coef = None
@@ -151,7 +174,7 @@ def make_inputs(cfg_id: int | dict, seed: int | None = None, layer: int = 0,
                 nzp = np.nonzero(key_coef[h])[0]
                 K[0, kv, nzp, :] += key_coef[h, nzp, None] * u[h][None, :]
 
-    out = Inputs(cfg=cfg, seed=seed, Q=f32_to_bf16_bits(Q), K=f32_to_bf16_bits(K), V=f32_to_bf16_bits(V),
+    out = Inputs(cfg=cfg, seed=seed, Q=_to_bf16_parallel(Q), K=_to_bf16_parallel(K), V=_to_bf16_parallel(V),
                  planted=planted, directions=directions, key_coef=key_coef)
     if cfg["plant"] == "norm":
         out.extra["norm_factor"] = cfg["norm_factor"]

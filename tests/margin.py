@@ -47,15 +47,18 @@ def enforce_margin(inp, ks, group_mode=0, rho=RHO, max_rounds=10, n_cand=64):
     ks = sorted(k for k in ks if k < L)
     Qw = orc.bf16_to_f64(inp.Q[0, :, first:, :])                       # [Hq,Lq,d]
     detect, accept = 1.5 * rho, 2.0 * rho
+    Kf = orc.bf16_to_f64(inp.K)                                         # kept in step with inp.K below
     for rnd in range(max_rounds):
-        s = orc.score(Qw[None], orc.bf16_to_f64(inp.K), Lq)
+        s = orc.score(Qw[None], Kf, Lq)
         sel = orc.group_scores(s, g) if group_mode == 1 else s
         margin = boundary_margin(sel, ks)
+        if L >= 32768:
+            print("  margin round %d: %.3g (target %.3g)" % (rnd, margin, 2 * rho), flush=True)
         if not ks or margin >= 2 * rho:
             return s, margin
         for kv in range(Hkv):
             heads = list(range(kv * g, (kv + 1) * g))
-            Kh = orc.bf16_to_f64(inp.K[0, kv])
+            Kh = Kf[0, kv]
             lse = np.stack([scipy.special.logsumexp(_window_logits(Qw[h], Kh, scale, first), axis=1) for h in heads])
             # selection rows that read this KV head, their thresholds
             rows = [sel[0, kv]] if group_mode == 1 else [sel[0, h] for h in heads]
@@ -76,13 +79,14 @@ def enforce_margin(inp, ks, group_mode=0, rho=RHO, max_rounds=10, n_cand=64):
             for attempt in range(40):
                 if todo.size == 0:
                     break
-                cand = gen.candidate_key_rows(inp, kv, pos[todo], n_cand)                 # [n, c, d] bits
+                nc = max(n_cand, min(4096, 16384 // todo.size))
+                cand = gen.candidate_key_rows(inp, kv, pos[todo], nc)                     # [n, c, d] bits
                 cf = orc.bf16_to_f64(cand)
                 # score of each candidate under each head, window log-sum-exp held fixed
                 vis = (first + np.arange(Lq))[None, :] >= pos[todo][:, None]             # [n, Lq]
                 sc = []
                 for j, h in enumerate(heads):
-                    x = scale * np.einsum("ncd,qd->ncq", cf, Qw[h]) - lse[j][None, None, :]
+                    x = scale * (cf @ Qw[h].T) - lse[j][None, None, :]                  # [n, c, Lq]
                     sc.append((np.exp(x) * vis[:, None, :]).sum(axis=2))
                 sc = np.stack(sc)                                                         # [g, n, c]
                 if group_mode == 1:
@@ -97,5 +101,6 @@ def enforce_margin(inp, ks, group_mode=0, rho=RHO, max_rounds=10, n_cand=64):
                 done = np.nonzero(has)[0]
                 if done.size:
                     gen.set_key_rows(inp, kv, pos[todo[done]], cand[done, pick[done]])
+                    Kf[0, kv, pos[todo[done]]] = cf[done, pick[done]]
                 todo = todo[~has]
     raise AssertionError("selection margin not reached after %d rounds" % max_rounds)

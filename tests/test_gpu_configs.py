@@ -1,0 +1,157 @@
+"""GPU parity at the five workloads' full sizes, in the launch configuration bench.py times
+(tsa_forward through the C ABI, inputs resident on the GPU).
+
+What the oracle can compute in full is compared in full: scores, index sets (bit-exact, the
+inputs carry a margin at every k of the sweep), the zero rows of the decompressed output.
+Attention outputs are compared in full where the oracle finishes in seconds (workloads 1-2)
+and on sampled compacted rows per head otherwise (first 8, last 8, 48 seeded random rows: each
+sampled row is an exact O(k d) computation of the oracle)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tsa_oracle as orc
+from paper_2602_03216_amd import inputs as gen
+from tests import gpu_util as gu
+from tests.margin import enforce_margin, RHO
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tsa():
+    from paper_2602_03216_amd import binding
+    binding.load_library(build_if_missing=False)
+    return binding
+
+
+def _sample_rows(k, seed):
+    r = np.random.Generator(np.random.PCG64(seed))
+    rows = set(range(min(8, k))) | set(range(max(0, k - 8), k))
+    if k > 16:
+        rows |= set(r.choice(k, size=min(48, k), replace=False).tolist())
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def _check_forward(tsa, inp, k, Q, K, V, s_ref, full_attend, block=None, group_mode=0):
+    cfg = inp.cfg
+    B, Hq, Hkv, L, d, Lq = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"]
+    g = Hq // Hkv
+    Hs = Hkv if group_mode else Hq
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq, group_mode=group_mode)
+    ws = tsa.alloc_workspace(desc, k, gu.DEV)
+    O = torch.full((B, Hq, L, d), 5.0, dtype=torch.bfloat16, device=gu.DEV)
+    idx = torch.zeros((B, Hs, k), dtype=torch.int32, device=gu.DEV)
+    kw = {}
+    bl = None
+    if block is not None:
+        bl = orc.lambda_block_list(k, block["block_size"], block["window"], 1)
+        kw = dict(block_list=torch.from_numpy(bl).to(gu.DEV), block_size=block["block_size"], max_blocks_per_row=bl.shape[1])
+    tsa.tsa_forward(desc, Q, K, V, k, O, ws, idx_out=idx, **kw)
+    torch.cuda.synchronize()
+    # index sets: bit-exact
+    sel_scores = orc.group_scores(s_ref, g) if group_mode else s_ref
+    widx, winv = orc.select(sel_scores, k)
+    got_idx = idx.cpu().numpy()
+    assert np.array_equal(got_idx, widx), "index sets differ at k=%d" % k
+    # zero rows: every unselected row of O is exactly zero, checked in full on the GPU result
+    Ob = gu.from_dev(O)
+    sel_mask = np.repeat(winv >= 0, Hq // Hs, axis=1)
+    assert not Ob[~sel_mask].any()
+    # attention output
+    if full_attend:
+        Qc, Kc, Vc = orc.compress(inp.Q, inp.K, inp.V, widx, group_mode)
+        want = orc.f64_to_bf16(orc.attend(orc.bf16_to_f64(Qc), orc.bf16_to_f64(Kc), orc.bf16_to_f64(Vc),
+                                          block_list=bl, block_size=block["block_size"] if block else 0))
+        return gu.assert_output_close(Ob[sel_mask].reshape(B, Hq, k, d), want, "forward k=%d" % k)
+    rows = _sample_rows(k, 1000 + k)
+    worst = (0.0, 0.0)
+    for h in range(Hq):
+        hs = h // (Hq // Hs)
+        toks = widx[0, hs]
+        Qh = orc.bf16_to_f64(inp.Q[0, h, toks])[None, None]
+        Kh = orc.bf16_to_f64(inp.K[0, h // g, toks])[None, None]
+        Vh = orc.bf16_to_f64(inp.V[0, h // g, toks])[None, None]
+        want = orc.f64_to_bf16(orc.attend(Qh, Kh, Vh, rows=rows, block_list=bl,
+                                          block_size=block["block_size"] if block else 0))[0, 0]
+        e = gu.assert_output_close(Ob[0, h, toks[rows]], want, "forward k=%d head %d (sampled rows)" % (k, h))
+        worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+    return worst
+
+
+def _run_config(tsa, cfg_id, full_attend, taus=None, group_mode=0):
+    inp = gen.make_inputs(cfg_id)
+    cfg = inp.cfg
+    taus = cfg["taus"] if taus is None else taus
+    ks = [orc.keep_count(cfg["L"], t) for t in taus]
+    s_ref, margin = enforce_margin(inp, ks, group_mode)
+    assert margin >= 2 * RHO
+    Q, K, V = gu.to_dev(inp.Q), gu.to_dev(inp.K), gu.to_dev(inp.V)
+    # scores through tsa_score, against the oracle's, in full
+    desc = tsa.make_desc(cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"])
+    s = torch.empty((cfg["B"], cfg["Hq"], cfg["L"]), dtype=torch.float32, device=gu.DEV)
+    tsa.tsa_score(desc, Q, K, s, tsa.alloc_workspace(desc, 1, gu.DEV))
+    gu.assert_scores_close(s.cpu().numpy(), s_ref, "scores of workload %s" % cfg["name"])
+    del s
+    for k in ks:
+        err = _check_forward(tsa, inp, k, Q, K, V, s_ref, full_attend, group_mode=group_mode)
+        print("workload %s k_keep=%d: max|dO| %.4g mean|dO| %.4g margin %.3g" % (cfg["name"], k, err[0], err[1], margin), flush=True)
+    return inp
+
+
+def test_workload1_tiny_mha(tsa):
+    inp = _run_config(tsa, 1, full_attend=True)
+    # all planted tokens are among the selected ones
+    s = orc.score(orc.bf16_to_f64(inp.Q), orc.bf16_to_f64(inp.K), 64)
+    idx, _ = orc.select(s, 256)
+    assert all(np.isin(inp.planted[h], idx[0, h]).all() for h in range(4))
+
+
+def test_workload2_mha_8k(tsa):
+    _run_config(tsa, 2, full_attend=True, taus=(0.75,))
+    _run_config(tsa, 2, full_attend=False, taus=(0.5,))
+
+
+def test_workload3_gqa_32k(tsa):
+    _run_config(tsa, 3, full_attend=False)
+
+
+def test_workload3_gqa_32k_group_mode(tsa):
+    _run_config(tsa, 3, full_attend=False, taus=(0.75,), group_mode=1)
+
+
+def test_workload4_gqa_128k(tsa):
+    _run_config(tsa, 4, full_attend=False)
+
+
+def test_workload5_interleaved_stack(tsa):
+    """Four layers, each reselecting tokens from fresh Q/K/V, composed with the sink + sliding
+    window block mask in compacted index space, output added into the residual stream."""
+    cfg0 = gen.CONFIGS[5]
+    k = orc.keep_count(cfg0["L"], cfg0["taus"][0])
+    block = dict(block_size=cfg0["block_size"], window=cfg0["window"])
+    x_bits = gen.make_residual(cfg0, gen.SEED_BASE + 5000)
+    x = gu.to_dev(x_bits)
+    prev = None
+    tok_check = np.random.Generator(np.random.PCG64(55)).choice(cfg0["L"], size=64, replace=False)
+    for layer in range(cfg0["layers"]):
+        inp = gen.make_inputs(5, layer=layer, prev_planted=prev)
+        prev = inp.planted
+        cfg = inp.cfg
+        s_ref, margin = enforce_margin(inp, [k])
+        assert margin >= 2 * RHO
+        Q, K, V = gu.to_dev(inp.Q), gu.to_dev(inp.K), gu.to_dev(inp.V)
+        err = _check_forward(tsa, inp, k, Q, K, V, s_ref, False, block=block)
+        # same layer again, this time straight into the residual stream
+        desc = tsa.make_desc(cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"])
+        bl = orc.lambda_block_list(k, block["block_size"], block["window"], 1)
+        O = torch.empty((cfg["B"], cfg["Hq"], cfg["L"], cfg["d"]), dtype=torch.bfloat16, device=gu.DEV)
+        x_before = x[0, tok_check].clone()
+        tsa.tsa_forward(desc, Q, K, V, k, O, tsa.alloc_workspace(desc, k, gu.DEV), residual=x,
+                        block_list=torch.from_numpy(bl).to(gu.DEV), block_size=block["block_size"], max_blocks_per_row=bl.shape[1])
+        torch.cuda.synchronize()
+        # residual rows of sampled tokens: x_new = bf16(x_old + O) where O is zero for unselected (token, head)
+        want = (x_before.float() + O[0, :, tok_check].permute(1, 0, 2).reshape(len(tok_check), -1).float()).bfloat16()
+        assert torch.equal(x[0, tok_check], want)
+        print("stack layer %d: max|dO| %.4g mean|dO| %.4g margin %.3g" % (layer, err[0], err[1], margin), flush=True)
+        del Q, K, V, O
