@@ -4,14 +4,20 @@ from __future__ import annotations
 import os
 import shutil
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
+OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libtsa.so")
 SOURCES = ["api.hip", "score.hip", "select.hip", "gather_scatter.hip", "attend.hip"]
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 instructions.
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+# per-file additions (attend: let the register allocator place MFMA results in VGPRs or AGPRs
+# per instruction instead of forcing every accumulator into AGPRs)
+EXTRA = {"attend.hip": os.environ.get("TSA_ATTEND_FLAGS", "-mllvm -amdgpu-mfma-vgpr-form").split()}
+_NOISE = "packed-fp32-ops"
 
 
 def hipcc_path() -> str:
@@ -21,15 +27,30 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found: libtsa cannot be built")
 
 
-def build_library(verbose: bool = False) -> str:
-    cmd = [hipcc_path(), *FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB_PATH + ".tmp"]
+def _run(cmd):
     proc = subprocess.run(cmd, capture_output=True, text=True)
-    noise = "packed-fp32-ops"
-    err = "\n".join(l for l in proc.stderr.splitlines() if noise not in l)
+    err = "\n".join(l for l in proc.stderr.splitlines() if _NOISE not in l)
     if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err.strip():
-        print(err)
+        raise RuntimeError("command failed: %s\n%s" % (" ".join(cmd), err))
+    return err
+
+
+def build_library(verbose: bool = False) -> str:
+    hipcc = hipcc_path()
+    os.makedirs(OBJ_DIR, exist_ok=True)
+
+    def compile_one(src):
+        obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
+        return obj, _run([hipcc, *FLAGS, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj])
+
+    with ThreadPoolExecutor(max_workers=len(SOURCES)) as pool:
+        results = list(pool.map(compile_one, SOURCES))
+    msgs = [m for _, m in results if m.strip()]
+    msgs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *[o for o, _ in results], "-o", LIB_PATH + ".tmp"]))
+    if verbose:
+        for m in msgs:
+            if m.strip():
+                print(m)
     os.replace(LIB_PATH + ".tmp", LIB_PATH)
     return LIB_PATH
 

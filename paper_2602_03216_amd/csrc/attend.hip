@@ -1,30 +1,45 @@
 // Causal attention over the compacted token set (Section 2.2, Stage 1: the attention
 // operation on Q^, K^, V^ with cost O(L'^2 d)), also used unchanged as the dense baseline.
-// Flash-style: one workgroup owns 128 query rows (4 wavefronts x 32 rows), streams 64-key
-// tiles of K and V through LDS, keeps the running max / sum and the output accumulator in
-// registers (online softmax), and never materialises the score matrix.
+//
+// Flash-style: one workgroup owns 256 query rows (4 wavefronts x 64 rows, one wavefront per
+// SIMD with the whole 512-entry register file), streams 64-key tiles of K and V through a
+// two-deep LDS ring, keeps the running max / sum and the output accumulator in registers
+// (online softmax) and never materialises the score matrix.
 //
 // Both products run on v_mfma_f32_32x32x16_bf16 in the TRANSPOSED orientation:
-//   S^T = K Q^T   rows = keys, cols = queries  -> a lane owns ONE query (col) and 32 of the 64
-//                 keys of the tile, so the row max / row sum of the softmax need a single
-//                 cross-lane step (lane <-> lane^32);
+//   S^T = K Q^T   rows = keys, cols = queries  -> a lane owns ONE query per 32-row sub-tile and
+//                 32 of the 64 keys of the tile: the row max / row sum of the softmax need a
+//                 single cross-lane step (lane <-> lane^32);
 //   O^T = V^T P^T rows = d, cols = queries     -> the P^T operand is exactly what the lane
-//                 already holds (its query, eight keys per MFMA step), no shuffle or LDS
+//                 already holds (its query, eight keys per MFMA step): no shuffle and no LDS
 //                 round trip for P, and the rescale factor of O is the lane's own.
-// The price is that V must be read with the key index contiguous.  V tiles are transposed on
-// their way into LDS (4 keys x 8 d per thread, 16-bit shuffles in registers) and stored with
-// the keys of each group of 16 permuted into the order in which the S^T accumulator holds
-// them, so that one 16-byte LDS read yields one MFMA operand.
+// Every K / V fragment read from LDS feeds two MFMAs (the wavefront's two query sub-tiles):
+// LDS delivers 128 B/clk per CU, and one operand per MFMA from LDS would need all of it.
+// V stays row-major in LDS; the V^T operand comes from ds_read_b64_tr_b16, which hands each
+// lane four keys of one d-column.
+// The loop is software-pipelined: the QK product of tile t+1 is issued together with the
+// softmax arithmetic of tile t, so the matrix pipe and the vector ALU overlap inside the one
+// wavefront a SIMD holds.  The O rescale is lazy: the running max is only raised when a row's
+// new max exceeds it by more than 2^8, so most tiles skip the 128-register multiply; the
+// final division by the row sum makes the result independent of the max actually used.
 #include "tsa_internal.h"
+
+#include <climits>
+
+#ifndef TSA_PROBE
+#define TSA_PROBE 0   // >0: timing probes that drop parts of the softmax arithmetic (results are wrong)
+#endif
 
 namespace tsa {
 
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int BM = 128;        // query rows per workgroup
+constexpr int BM = 256;        // query rows per workgroup (64 per wavefront)
 constexpr int BN = 64;         // keys per tile
+constexpr int kBlock = 128;    // block size of a block list (two key tiles, half a query tile)
 constexpr float kNegBig = -1.0e30f;
+constexpr float kLazy = 8.0f;  // log2 units the running max may lag behind
 
 struct AttendArgs {
   const __bf16* Q;
@@ -45,14 +60,177 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+__device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p);
+}
+
+// Key tiles a workgroup visits, in order.  `use` bit 0: the first 128 query rows of the
+// workgroup take part, bit 1: the last 128 (they can differ only under a block list).
+struct Tile {
+  int k0;      // first key of the tile, < 0: no more tiles
+  int use;
+};
+
+struct TileGen {
+  const int32_t* la;
+  const int32_t* lb;
+  int ca, cb, ia, ib, sub, kb, use;
+  int plain_n, plain_i;
+  bool plain;
+  __device__ Tile next() {
+    if (plain) {
+      if (plain_i >= plain_n) return Tile{-1, 0};
+      Tile t{plain_i * BN, 3};
+      ++plain_i;
+      return t;
+    }
+    if (sub == 0) {
+      const int a = ia < ca ? la[ia] : INT_MAX, b = ib < cb ? lb[ib] : INT_MAX;
+      kb = min(a, b);
+      if (kb == INT_MAX) return Tile{-1, 0};
+      use = (a == kb ? 1 : 0) | (b == kb ? 2 : 0);
+      ia += (a == kb);
+      ib += (b == kb);
+      sub = 1;
+      return Tile{kb * kBlock, use};
+    }
+    sub = 0;
+    return Tile{kb * kBlock + BN, use};
+  }
+};
+
+__device__ __forceinline__ int count_valid(const int32_t* row, int max_blocks, int qb) {
+  int cnt = 0;
+  while (cnt < max_blocks) {
+    const int kb = row[cnt];
+    if (kb < 0 || kb > qb) break;
+    ++cnt;
+  }
+  return cnt;
+}
+
+// One 32-key half tile of S^T for the wavefront's two query sub-tiles: s[qs] (16 fp32 each).
 template <int D>
-__global__ __launch_bounds__(kThreads, 2) void attend_kernel(AttendArgs a) {
-  constexpr int KS = D + 8;            // K tile row stride (elements): 16-byte pad spreads rows over banks
-  constexpr int VS = BN + 8;           // V^T tile row stride
-  constexpr int KCH = BN * (D / 8) / kThreads;   // 16-byte K chunks per thread per tile
-  constexpr bool kVAll = (D == 128);   // every thread has a V transpose task (D=64: half of them)
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[BN * KS];
-  __shared__ __attribute__((aligned(16))) __bf16 Vt[D * VS];
+__device__ __forceinline__ void qk_half(const __bf16* Kt_half, int k_rd, const bf16x8 (&qf)[2][D / 16], f32x16 (&s)[2]) {
+  constexpr int KS = D + 8;
+  f32x16 acc0 = {0}, acc1 = {0};
+#pragma unroll
+  for (int st = 0; st < D / 16; ++st) {
+    const bf16x8 kf = *(const bf16x8*)(&Kt_half[k_rd + 16 * st]);
+    acc0 = mfma32(kf, qf[0][st], acc0);
+    acc1 = mfma32(kf, qf[1][st], acc1);
+  }
+  s[0] = acc0;
+  s[1] = acc1;
+  (void)KS;
+}
+
+// O^T += V^T P^T for one 32-key half tile (two MFMA k-steps of 16 keys), both query sub-tiles.
+template <int D>
+__device__ __forceinline__ void pv_half(const __bf16* Vt_half, int v_rd, const uint32_t (&pb)[2][8], f32x16 (&o)[2][D / 32]) {
+  constexpr int KS = D + 16;                        // V tile row stride
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf) {
+    const u32x4 pw0 = {pb[0][4 * hf + 0], pb[0][4 * hf + 1], pb[0][4 * hf + 2], pb[0][4 * hf + 3]};
+    const u32x4 pw1 = {pb[1][4 * hf + 0], pb[1][4 * hf + 1], pb[1][4 * hf + 2], pb[1][4 * hf + 3]};
+    const bf16x8 pf0 = __builtin_bit_cast(bf16x8, pw0);
+    const bf16x8 pf1 = __builtin_bit_cast(bf16x8, pw1);
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt) {
+      const bf16x4 v0 = lds_read_tr(&Vt_half[v_rd + (16 * hf) * KS + 32 * dt]);
+      const bf16x4 v1 = lds_read_tr(&Vt_half[v_rd + (16 * hf + 8) * KS + 32 * dt]);
+      const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+      o[0][dt] = mfma32(vf, pf0, o[0][dt]);
+      o[1][dt] = mfma32(vf, pf1, o[1][dt]);
+    }
+  }
+}
+
+// Row max of one half tile (per query sub-tile), in scaled log2 units.
+__device__ __forceinline__ void row_max(const f32x16 (&s)[2], float c, float (&mxc)[2]) {
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs) {
+    float mx = s[qs][0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[qs][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mxc[qs] = mx * c;
+  }
+}
+
+// Raises the running max (and rescales l, O) only when some row outgrew it by more than kLazy.
+template <int ND>
+__device__ __forceinline__ void raise_max(const float (&mxc)[2], float (&m)[2], float (&l)[2], f32x16 (&o)[2][ND]) {
+  if (__any(mxc[0] > m[0] + kLazy || mxc[1] > m[1] + kLazy)) {
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+      const float mn = fmaxf(m[qs], mxc[qs]);
+      const float alpha = fast_exp2(m[qs] - mn);
+      m[qs] = mn;
+      l[qs] *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[qs][dt][r] *= alpha;
+    }
+  }
+}
+
+template <int ND>
+__device__ __forceinline__ void softmax_max(const f32x16 (&s)[2], float c, float (&m)[2], float (&l)[2], f32x16 (&o)[2][ND]) {
+  float mxc[2];
+  row_max(s, c, mxc);
+  raise_max<ND>(mxc, m, l, o);
+}
+
+// p = exp2(s*c - m), packed to bf16 pairs in accumulator order; row sums into l.
+__device__ __forceinline__ void softmax_exp(const f32x16 (&s)[2], float c, const float (&m)[2], float (&l)[2], uint32_t (&pb)[2][8]) {
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs) {
+    const float mq = m[qs];
+    float ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      const float p0 = fast_exp2(fmaf(s[qs][r], c, -mq));
+      const float p1 = fast_exp2(fmaf(s[qs][r + 1], c, -mq));
+      ps0 += p0;
+      ps1 += p1;
+      pb[qs][r >> 1] = pack_bf16(p0, p1);
+    }
+    l[qs] += ps0 + ps1;
+  }
+}
+
+__device__ __forceinline__ void mask_half(f32x16 (&s)[2], int key0, int hi, int qrow0) {
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (key0 + c_row(r, hi) > qrow0 + 32 * qs) s[qs][r] = -INFINITY;
+}
+
+// Raw buffer descriptor over one head's rows: loads past `bytes` return zero, so ragged tails
+// and tiles beyond the end need no bounds arithmetic in the loop.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const __bf16* base, long long bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads, 1) void attend_kernel(AttendArgs a) {
+  // LDS row strides in elements.  K rows are read 16 bytes per lane by 16 lanes of consecutive
+  // keys: a 16-byte pad walks them over all 64 banks.  V rows are read by the transposing load,
+  // where 4 lanes cover 32 contiguous bytes of one key and the next 4 lanes the next key: a
+  // 32-byte pad keeps the four keys of a 16-lane group on disjoint banks.
+  constexpr int KS = D + 8;
+  constexpr int VS = D + 16;
+  constexpr int KTILE = BN * KS, VTILE = BN * VS; // elements of one staged tile
+  constexpr int CH = BN * (D / 8) / kThreads;     // 16-byte chunks per thread per tile
+  constexpr int NS = D / 16;                      // MFMA k-steps of the QK product
+  constexpr int ND = D / 32;                      // d sub-tiles of the output
+  constexpr int ROWB = D * 2;                     // bytes of one row in global memory
+  __shared__ __attribute__((aligned(16))) __bf16 smem[3 * KTILE + 2 * VTILE];   // K ring [3], V ring [2]
 
   // ---- workgroup -> (head, query tile).  Consecutive workgroup ids go to different XCDs, so
   // id % 8 picks the XCD; all tiles of a head (and all heads of a KV group) stay on one XCD to
@@ -67,185 +245,307 @@ __global__ __launch_bounds__(kThreads, 2) void attend_kernel(AttendArgs a) {
   const int h = (hr % a.kvh) * g + hr / a.kvh;           // heads of one KV group are 8 apart in hp
   const long long bh = (long long)b * a.Hq + h;
   const long long bkv = (long long)b * a.kvh + h / g;
+  const long long head_bytes = (long long)a.Lc * ROWB;
 
-  const __bf16* Qh = a.Q + bh * a.Lc * D;
-  const __bf16* Kh = a.K + bkv * a.Lc * D;
-  const __bf16* Vh = a.V + bkv * a.Lc * D;
+  const __amdgpu_buffer_rsrc_t Qr = head_rsrc(a.Q + bh * a.Lc * D, head_bytes);
+  const __amdgpu_buffer_rsrc_t Kr = head_rsrc(a.K + bkv * a.Lc * D, head_bytes);
+  const __amdgpu_buffer_rsrc_t Vr = head_rsrc(a.V + bkv * a.Lc * D, head_bytes);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int q0 = qt * BM;
-  const int qrow = q0 + 32 * wave + lo;                 // this lane's query (column of S^T and O^T)
+  const int wrow0 = q0 + 64 * wave;                      // first query row of this wavefront
+  const int half_bit = 1 << (wave >> 1);                 // which 128-row half the wavefront is in
+  const float c = a.c;
+  const float c_ = c;
 
-  // Q^T operand fragments stay in registers for the whole kernel
-  bf16x8 qf[D / 16];
-  {
-    const bool ok = qrow < a.Lc;
-    const __bf16* row = Qh + (long long)(ok ? qrow : 0) * D + 8 * hi;
+  // Q^T operand fragments (two 32-row sub-tiles) stay in registers for the whole kernel
+  bf16x8 qf[2][NS];
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) {
-      bf16x8 v = *(const bf16x8*)(row + 16 * s);
-      if (!ok) v = bf16x8{};
-      qf[s] = v;
+  for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(Qr, (wrow0 + 32 * qs + lo) * ROWB + 16 * hi + 32 * s, 0, 0);
+      qf[qs][s] = __builtin_bit_cast(bf16x8, v);
+    }
+
+  TileGen gen;
+  gen.plain = a.block_list == nullptr;
+  gen.plain_i = 0;
+  gen.plain_n = (min(q0 + BM, a.Lc) + BN - 1) / BN;
+  gen.ia = gen.ib = gen.sub = gen.kb = gen.use = gen.ca = gen.cb = 0;
+  gen.la = gen.lb = nullptr;
+  if (!gen.plain) {
+    const int nqb = (a.Lc + kBlock - 1) / kBlock;
+    const int qa = 2 * qt, qb = 2 * qt + 1;
+    gen.la = a.block_list + (long long)qa * a.max_blocks;
+    gen.ca = count_valid(gen.la, a.max_blocks, qa);
+    if (qb < nqb) {
+      gen.lb = a.block_list + (long long)qb * a.max_blocks;
+      gen.cb = count_valid(gen.lb, a.max_blocks, qb);
     }
   }
 
-  // ---- which key tiles this workgroup visits
-  int n_tiles;
-  const int32_t* bl_row = nullptr;
-  if (a.block_list) {
-    bl_row = a.block_list + (long long)qt * a.max_blocks;
-    int cnt = 0;
-    while (cnt < a.max_blocks) {
-      const int kb = bl_row[cnt];
-      if (kb < 0 || kb > qt) break;
-      ++cnt;
+  // ---- staging: global -> registers -> LDS, 16-byte chunks, same layout for K and V.
+  // Thread chunk i covers row st_row + i * kRowsPerPass, columns 8*st_col..; the tile's first key
+  // goes into the scalar offset of the buffer load.
+  constexpr int kRowsPerPass = kThreads / (D / 8);
+  const int st_row = tid / (D / 8), st_col = tid % (D / 8);
+  const int g_off = st_row * ROWB + 16 * st_col;                  // bytes, global side
+  const int lk_off = st_row * KS + 8 * st_col;                    // elements, LDS side (K layout)
+  const int lv_off = st_row * VS + 8 * st_col;                    // elements, LDS side (V layout)
+  auto load_tile = [&](__amdgpu_buffer_rsrc_t r, int k0, u32x4 (&reg)[CH]) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i)
+      reg[i] = __builtin_amdgcn_raw_buffer_load_b128(r, g_off + i * kRowsPerPass * ROWB, k0 * ROWB, 0);
+  };
+  auto store_k = [&](__bf16* dst, const u32x4 (&reg)[CH]) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) *(u32x4*)(&dst[lk_off + i * kRowsPerPass * KS]) = reg[i];
+  };
+  auto store_v = [&](__bf16* dst, const u32x4 (&reg)[CH]) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) *(u32x4*)(&dst[lv_off + i * kRowsPerPass * VS]) = reg[i];
+  };
+
+  // LDS read bases.  K operand (A of S^T): row = key (lo), 8 d-values at 8*hi.
+  const int k_rd = lo * KS + 8 * hi;
+  // V^T operand via transposing read: lane r of a 16-lane group points at key 4*hi + (r>>2),
+  // d = 16*(lo>>4) + 4*(r&3); the group gets d = 16*(lo>>4) + (lane&15), four consecutive keys.
+  const int v_rd = (4 * hi + ((lane & 15) >> 2)) * VS + 16 * (lo >> 4) + 4 * (lane & 3);
+
+  f32x16 o[2][ND];
+#pragma unroll
+  for (int qs = 0; qs < 2; ++qs)
+#pragma unroll
+    for (int dt = 0; dt < ND; ++dt) o[qs][dt] = f32x16{0};
+  float m[2] = {kNegBig, kNegBig}, l[2] = {0.f, 0.f};
+
+  // ring slots: K(t) in kc, K(t+1) in kn, K(t+2) goes to kf; V(t) in vc, V(t+1) goes to vn
+  __bf16* kc = smem;
+  __bf16* kn = smem + KTILE;
+  __bf16* kf = smem + 2 * KTILE;
+  __bf16* vc = smem + 3 * KTILE;
+  __bf16* vn = smem + 3 * KTILE + VTILE;
+  auto rotate = [&]() {
+    __bf16* t = kc; kc = kn; kn = kf; kf = t;
+    t = vc; vc = vn; vn = t;
+  };
+
+  // ---- prologue
+  Tile T0 = gen.next(), T1 = gen.next(), T2 = gen.next();
+  u32x4 kreg[CH], vreg[CH];
+  f32x16 sA[2], sB[2];
+  uint32_t pA[2][8], pB[2][8];
+  if (T0.k0 >= 0) {
+    load_tile(Kr, T0.k0, kreg);
+    load_tile(Vr, T0.k0, vreg);
+    store_k(kc, kreg);
+    store_v(vc, vreg);
+    if (T1.k0 >= 0) {
+      load_tile(Kr, T1.k0, kreg);
+      store_k(kn, kreg);
     }
-    n_tiles = 2 * cnt;                                   // a 128-token block is two key tiles
-  } else {
-    n_tiles = (min(q0 + BM, a.Lc) + BN - 1) / BN;
   }
-  auto tile_start = [&](int it) -> int {
-    return bl_row ? (bl_row[it >> 1] * 2 + (it & 1)) * BN : it * BN;
-  };
+  __syncthreads();
+  auto wave_active = [&](const Tile& t) -> bool { return t.k0 >= 0 && (t.use & half_bit) && t.k0 <= wrow0 + 63; };
+  if (T0.k0 >= 0) qk_half<D>(kc, k_rd, qf, sA);
+  if (T2.k0 >= 0) load_tile(Kr, T2.k0, kreg);
+  if (T1.k0 >= 0) load_tile(Vr, T1.k0, vreg);
+  if (wave_active(T0)) {
+    if (T0.k0 + 31 > wrow0) mask_half(sA, T0.k0, hi, wrow0 + lo);
+    softmax_max<ND>(sA, c, m, l, o);
+  }
 
-  // ---- staging: global -> registers (prefetch) -> LDS
-  u32x4 kreg[KCH];
-  u32x4 vreg[4];
-  const int v_kq = tid & 15, v_do = tid >> 4;            // key quad 0..15, d octet
-  const bool v_on = kVAll || v_do < D / 8;
-  auto load_tile = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      const int c = tid + kThreads * i;
-      const int row = c / (D / 8), col8 = c % (D / 8);
-      const int key = k0 + row;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (key < a.Lc) v = *(const u32x4*)(Kh + (long long)key * D + 8 * col8);
-      kreg[i] = v;
-    }
-    if (v_on) {
-#pragma unroll
-      for (int cc = 0; cc < 4; ++cc) {
-        const int key = k0 + 4 * v_kq + cc;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (key < a.Lc) v = *(const u32x4*)(Vh + (long long)key * D + 8 * v_do);
-        vreg[cc] = v;
+  // Invariant at the top of an iteration: sA = S^T of the first half of tile T0, already masked
+  // and already covered by the running max m (if this wavefront takes part in T0); K(T0) in kc,
+  // K(T1) in kn, V(T0) in vc; kreg = K(T2) and vreg = V(T1) are in flight.
+  //
+  // Order inside an iteration: every block of 16 MFMAs is issued next to vector work that does
+  // not depend on it, so the matrix pipe and the VALU overlap within the wavefront:
+  //   QK(T0, half 1)      with  exp(sA)
+  //   PV(T0, half 0)      with  max(sB)            [then the rare raise of m, rescale of O]
+  //   QK(T1, half 0)      with  exp(sB)
+  //   PV(T0, half 1)      with  max(sA of T1), staging  [then the rare raise of m]
+
+  // ---- plain causal mode: tiles that lie entirely below the workgroup's first row need no mask
+  // and no per-wavefront decisions; loads past the end return zeros, so nothing in this loop is
+  // conditional except the rare raise of the running max.
+  if (gen.plain) {
+    const int n_fast = q0 / BN - 1;                      // T0 and T1 both below the diagonal
+    int t = 0;
+    // The iteration is a stream of 32 chunks of two MFMAs each:
+    //    0.. 7  S^T(T0, half 1) -> sB      with  exp(sA) -> pA
+    //    8..15  O^T += V^T(T0, half 0) pA  with  row max of sB          [then the rare raise of m]
+    //   16..23  S^T(T1, half 0) -> sA      with  exp(sB) -> pB
+    //   24..31  O^T += V^T(T0, half 1) pB  with  row max of sA, staging  [barrier, rare raise of m]
+    // Each chunk consumes one 16-byte LDS fragment per lane (a K fragment, or a V^T fragment from
+    // two transposing reads); fragments are fetched kPF chunks ahead through a small register
+    // ring that runs across the blocks and across iterations, so the LDS latency is hidden even
+    // though the SIMD holds a single wavefront.
+    constexpr int kPF = 3, kRing = 4, kChunks = 4 * NS;
+    static_assert(NS == 8 || NS == 4, "chunk stream is laid out for d = 128 or 64");
+    constexpr int CPB = kChunks / 4;                       // chunks per block
+    bf16x8 kfr[kRing];
+    bf16x4 vfl[kRing], vfh[kRing];
+    // fragment fetch for chunk c of the iteration whose tiles sit in (kc_, kn_, vc_)
+    auto fetch = [&](int c, const __bf16* kc_, const __bf16* kn_, const __bf16* vc_) {
+      const int blk = c / CPB, i = c % CPB, slot = c % kRing;
+      if (blk == 0) kfr[slot] = *(const bf16x8*)(&kc_[32 * KS + k_rd + 16 * i]);
+      else if (blk == 2) kfr[slot] = *(const bf16x8*)(&kn_[k_rd + 16 * i]);
+      else {
+        const int hf = i / ND, dt = i % ND;
+        const __bf16* vt = vc_ + (blk == 3 ? 32 * VS : 0);
+        vfl[slot] = lds_read_tr(&vt[v_rd + (16 * hf) * VS + 32 * dt]);
+        vfh[slot] = lds_read_tr(&vt[v_rd + (16 * hf + 8) * VS + 32 * dt]);
       }
-    }
-  };
-  auto store_tile = [&]() {
+    };
+    if (n_fast > 0) {
 #pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      const int c = tid + kThreads * i;
-      const int row = c / (D / 8), col8 = c % (D / 8);
-      *(u32x4*)(&Ks[row * KS + 8 * col8]) = kreg[i];
+      for (int c = 0; c < kPF; ++c) fetch(c, kc, kn, vc);
     }
-    if (v_on) {
-      // 4 keys x 8 d  ->  8 d x 4 keys; the quad goes to its permuted slot inside the group of 16 keys
-      const int grp = v_kq >> 2, c4 = v_kq & 3;
-      const int col = 16 * grp + 4 * (2 * (c4 & 1) + (c4 >> 1));
+    for (; t < n_fast; ++t) {
+      float mxc[2], mx[2], ps[2];
+      f32x16 acc0, acc1;
+      const int kload = (t + 3) * BN * ROWB, vload = (t + 2) * BN * ROWB;
 #pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {                   // dword e2 holds d = 2*e2, 2*e2+1
-        const uint32_t k0 = vreg[0][e2], k1 = vreg[1][e2], k2 = vreg[2][e2], k3 = vreg[3][e2];
-        u32x2 even, odd;
-        even[0] = __builtin_amdgcn_perm(k1, k0, 0x05040100u);   // (k0.lo, k1.lo)
-        even[1] = __builtin_amdgcn_perm(k3, k2, 0x05040100u);
-        odd[0] = __builtin_amdgcn_perm(k1, k0, 0x07060302u);    // (k0.hi, k1.hi)
-        odd[1] = __builtin_amdgcn_perm(k3, k2, 0x07060302u);
-        *(u32x2*)(&Vt[(8 * v_do + 2 * e2) * VS + col]) = even;
-        *(u32x2*)(&Vt[(8 * v_do + 2 * e2 + 1) * VS + col]) = odd;
+      for (int c = 0; c < kChunks; ++c) {
+        const int blk = c / CPB, i = c % CPB, slot = c % kRing;
+        // prefetch kPF chunks ahead; the first chunks of the next iteration read the rotated slots
+        if (c + kPF < kChunks) fetch(c + kPF, kc, kn, vc);
+        else fetch(c + kPF - kChunks, kn, kf, vn);
+        if (blk == 0 || blk == 2) {
+          const f32x16 (&s_in)[2] = blk == 0 ? sA : sB;
+          uint32_t (&p_out)[2][8] = blk == 0 ? pA : pB;
+          if (i == 0) { acc0 = f32x16{0}; acc1 = f32x16{0}; ps[0] = ps[1] = 0.f; }
+          constexpr int EPS = 16 / NS;
+          // one MFMA, then the exponentials of one query sub-tile: the vector work runs in the
+          // shadow of the MFMA that was just issued
+#pragma unroll
+          for (int qs = 0; qs < 2; ++qs) {
+            if (qs == 0) acc0 = mfma32(kfr[slot], qf[0][i], acc0);
+            else acc1 = mfma32(kfr[slot], qf[1][i], acc1);
+#pragma unroll
+            for (int e = 0; e < EPS; e += 2) {
+              const int r = EPS * i + e;
+#if TSA_PROBE >= 3
+              p_out[qs][r >> 1] = __float_as_uint(s_in[qs][r]);
+              continue;
+#endif
+#if TSA_PROBE >= 1
+              const float p0 = s_in[qs][r] * c_, p1 = s_in[qs][r + 1] * c_;
+#else
+              const float p0 = fast_exp2(fmaf(s_in[qs][r], c_, -m[qs]));
+              const float p1 = fast_exp2(fmaf(s_in[qs][r + 1], c_, -m[qs]));
+#endif
+#if TSA_PROBE < 2
+              ps[qs] += p0 + p1;
+#endif
+              p_out[qs][r >> 1] = pack_bf16(p0, p1);
+            }
+            if (qs == 0) __builtin_amdgcn_sched_barrier(0);
+          }
+          if (i == CPB - 1) {
+            f32x16 (&s_out)[2] = blk == 0 ? sB : sA;
+            s_out[0] = acc0;
+            s_out[1] = acc1;
+            l[0] += ps[0];
+            l[1] += ps[1];
+          }
+        } else {
+          const f32x16 (&s_in)[2] = blk == 1 ? sB : sA;
+          const uint32_t (&pb)[2][8] = blk == 1 ? pA : pB;
+          const int hf = i / ND, dt = i % ND;
+          constexpr int EPC = 16 / CPB;
+          if (i == 0) { mx[0] = s_in[0][0]; mx[1] = s_in[1][0]; }
+          const u32x4 pw0 = {pb[0][4 * hf + 0], pb[0][4 * hf + 1], pb[0][4 * hf + 2], pb[0][4 * hf + 3]};
+          const u32x4 pw1 = {pb[1][4 * hf + 0], pb[1][4 * hf + 1], pb[1][4 * hf + 2], pb[1][4 * hf + 3]};
+          const bf16x8 vf = __builtin_shufflevector(vfl[slot], vfh[slot], 0, 1, 2, 3, 4, 5, 6, 7);
+          o[0][dt] = mfma32(vf, __builtin_bit_cast(bf16x8, pw0), o[0][dt]);
+#if TSA_PROBE < 2
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) mx[0] = fmaxf(mx[0], s_in[0][EPC * i + e]);
+#endif
+          __builtin_amdgcn_sched_barrier(0);
+          o[1][dt] = mfma32(vf, __builtin_bit_cast(bf16x8, pw1), o[1][dt]);
+#if TSA_PROBE < 2
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) mx[1] = fmaxf(mx[1], s_in[1][EPC * i + e]);
+#endif
+          if (blk == 3 && TSA_PROBE < 4) {                 // K(t+2) -> kf, V(t+1) -> vn, then refill the registers
+            if (i < CH) {
+              *(u32x4*)(&kf[lk_off + i * kRowsPerPass * KS]) = kreg[i];
+              kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, g_off + i * kRowsPerPass * ROWB, kload, 0);
+            } else if (i < 2 * CH) {
+              *(u32x4*)(&vn[lv_off + (i - CH) * kRowsPerPass * VS]) = vreg[i - CH];
+              vreg[i - CH] = __builtin_amdgcn_raw_buffer_load_b128(Vr, g_off + (i - CH) * kRowsPerPass * ROWB, vload, 0);
+            }
+          }
+          if (i == CPB - 1) {
+#pragma unroll
+            for (int qs = 0; qs < 2; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32)) * c_;
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (c == 2 * CPB - 1) raise_max<ND>(mxc, m, l, o);
       }
+#if TSA_PROBE < 5
+      __syncthreads();
+#endif
+      raise_max<ND>(mxc, m, l, o);
+      rotate();
     }
-  };
+    if (t > 0) {                                           // hand over to the general loop
+      auto tile_at = [&](int i) { return i < gen.plain_n ? Tile{i * BN, 3} : Tile{-1, 0}; };
+      T0 = tile_at(t); T1 = tile_at(t + 1); T2 = tile_at(t + 2);
+      gen.plain_i = t + 3;
+    }
+  }
 
-  f32x16 o[D / 32];
-#pragma unroll
-  for (int dt = 0; dt < D / 32; ++dt) o[dt] = f32x16{0};
-  float m = kNegBig, l = 0.f;
-
-  if (n_tiles > 0) load_tile(tile_start(0));
-  for (int it = 0; it < n_tiles; ++it) {
-    const int k0 = tile_start(it);
-    __syncthreads();                                     // everyone is done reading the previous tile
-    store_tile();
+  // ---- general loop: diagonal tiles (mask, wavefronts that have nothing to do) and block lists
+  while (T0.k0 >= 0) {
+    qk_half<D>(kc + 32 * KS, k_rd, qf, sB);
+    if (wave_active(T0)) {
+      if (T0.k0 + BN - 1 > wrow0) mask_half(sB, T0.k0 + 32, hi, wrow0 + lo);
+      softmax_exp(sA, c, m, l, pA);
+      pv_half<D>(vc, v_rd, pA, o);
+      softmax_max<ND>(sB, c, m, l, o);
+      softmax_exp(sB, c, m, l, pB);
+      pv_half<D>(vc + 32 * VS, v_rd, pB, o);
+    }
+    if (T1.k0 >= 0) qk_half<D>(kn, k_rd, qf, sA);
+    if (wave_active(T1)) {
+      if (T1.k0 + 31 > wrow0) mask_half(sA, T1.k0, hi, wrow0 + lo);
+      softmax_max<ND>(sA, c, m, l, o);
+    }
+    if (T2.k0 >= 0) store_k(kf, kreg);
+    if (T1.k0 >= 0) store_v(vn, vreg);
+    const Tile T3 = gen.next();
+    if (T3.k0 >= 0) load_tile(Kr, T3.k0, kreg);
+    if (T2.k0 >= 0) load_tile(Vr, T2.k0, vreg);
     __syncthreads();
-    if (it + 1 < n_tiles) load_tile(tile_start(it + 1)); // in flight during the math below
-
-    if (k0 > q0 + 32 * wave + 31) continue;              // every key of the tile is after this wave's rows
-    // ---- S^T = K Q^T : two 32-key sub-tiles
-    f32x16 st[2];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-      f32x16 acc = {0};
-#pragma unroll
-      for (int s = 0; s < D / 16; ++s) {
-        const bf16x8 kf = *(const bf16x8*)(&Ks[(32 * kt + lo) * KS + 16 * s + 8 * hi]);
-        acc = mfma32(kf, qf[s], acc);
-      }
-      st[kt] = acc;
-    }
-    if (k0 + BN - 1 > q0 + 32 * wave) {                  // tile crosses this wave's diagonal
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          if (k0 + 32 * kt + c_row(r, hi) > qrow) st[kt][r] = -INFINITY;
-    }
-    // ---- online softmax (log2 domain); lane and lane^32 share the query
-    float mx = st[0][0];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[kt][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float mn = fmaxf(m, mx * a.c);
-    const float alpha = fast_exp2(m - mn);
-    m = mn;
-    float psum = 0.f;
-    uint32_t pb[2][8];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        const float p0 = fast_exp2(fmaf(st[kt][r], a.c, -mn));
-        const float p1 = fast_exp2(fmaf(st[kt][r + 1], a.c, -mn));
-        psum += p0 + p1;
-        pb[kt][r >> 1] = pack_bf16(p0, p1);
-      }
-    l = l * alpha + psum;
-#pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-    // ---- O^T += V^T P^T : four steps of 16 keys
-#pragma unroll
-    for (int s4 = 0; s4 < 4; ++s4) {
-      const int kt = s4 >> 1, half = s4 & 1;
-      u32x4 pw = {pb[kt][4 * half + 0], pb[kt][4 * half + 1], pb[kt][4 * half + 2], pb[kt][4 * half + 3]};
-      const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt) {
-        const bf16x8 vf = *(const bf16x8*)(&Vt[(32 * dt + lo) * VS + 16 * s4 + 8 * hi]);
-        o[dt] = mfma32(vf, pf, o[dt]);
-      }
-    }
+    T0 = T1; T1 = T2; T2 = T3;
+    rotate();
   }
 
-  // ---- epilogue: normalise, round to bf16, store O[query][d] (this lane: 4 consecutive d per register quad)
-  const float lt = l + __shfl_xor(l, 32);
-  const float inv_l = 1.0f / lt;
-  if (qrow < a.Lc) {
-    __bf16* orow = a.O + (bh * a.Lc + qrow) * D;
+  // ---- epilogue: normalise, round to bf16, store O[query][d] (a lane holds 4 consecutive d per register quad)
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+  for (int qs = 0; qs < 2; ++qs) {
+    const int qrow = wrow0 + 32 * qs + lo;
+    const float lt = l[qs] + __shfl_xor(l[qs], 32);
+    const float inv_l = lt > 0.f ? 1.0f / lt : 0.f;
+    if (qrow < a.Lc) {
+      __bf16* orow = a.O + (bh * a.Lc + qrow) * D;
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        u32x2 w;
-        w[0] = pack_bf16(o[dt][4 * q4 + 0] * inv_l, o[dt][4 * q4 + 1] * inv_l);
-        w[1] = pack_bf16(o[dt][4 * q4 + 2] * inv_l, o[dt][4 * q4 + 3] * inv_l);
-        *(u32x2*)(orow + 32 * dt + 8 * q4 + 4 * hi) = w;
-      }
-    if (a.lse && hi == 0) a.lse[bh * a.Lc + qrow] = (m + log2f(lt)) * kLn2;
+      for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          u32x2 w;
+          w[0] = pack_bf16(o[qs][dt][4 * q4 + 0] * inv_l, o[qs][dt][4 * q4 + 1] * inv_l);
+          w[1] = pack_bf16(o[qs][dt][4 * q4 + 2] * inv_l, o[qs][dt][4 * q4 + 3] * inv_l);
+          *(u32x2*)(orow + 32 * dt + 8 * q4 + 4 * hi) = w;
+        }
+      if (a.lse && hi == 0) a.lse[bh * a.Lc + qrow] = (m[qs] + log2f(lt)) * kLn2;
+    }
   }
 }
 
