@@ -34,9 +34,12 @@ namespace tsa {
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int BM = 256;        // query rows per workgroup (64 per wavefront)
+constexpr int BM = 256;        // query rows per workgroup
 constexpr int BN = 64;         // keys per tile
+#ifndef TSA_QS
+#define TSA_QS 1
+#endif
+constexpr int kQS = TSA_QS;    // query sub-tiles per wavefront (see attend_kernel)
 constexpr int kBlock = 128;    // block size of a block list (two key tiles, half a query tile)
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLazy = 8.0f;  // log2 units the running max may lag behind
@@ -58,6 +61,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   v[0] = (__bf16)lo;
   v[1] = (__bf16)hi;
   return __builtin_bit_cast(uint32_t, v);
+}
+
+// Workgroup barrier that waits for this wavefront's LDS traffic only.  __syncthreads() also waits
+// for every outstanding global load, which would expose the latency of the tile prefetch that
+// was issued just before it; those loads land in registers and are consumed a tile later.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
@@ -112,46 +122,45 @@ __device__ __forceinline__ int count_valid(const int32_t* row, int max_blocks, i
 }
 
 // One 32-key half tile of S^T for the wavefront's two query sub-tiles: s[qs] (16 fp32 each).
-template <int D>
-__device__ __forceinline__ void qk_half(const __bf16* Kt_half, int k_rd, const bf16x8 (&qf)[2][D / 16], f32x16 (&s)[2]) {
-  constexpr int KS = D + 8;
-  f32x16 acc0 = {0}, acc1 = {0};
+template <int D, int QS>
+__device__ __forceinline__ void qk_half(const __bf16* Kt_half, int k_rd, const bf16x8 (&qf)[QS][D / 16], f32x16 (&s)[QS]) {
+#pragma unroll
+  for (int qs = 0; qs < QS; ++qs) s[qs] = f32x16{0};
 #pragma unroll
   for (int st = 0; st < D / 16; ++st) {
     const bf16x8 kf = *(const bf16x8*)(&Kt_half[k_rd + 16 * st]);
-    acc0 = mfma32(kf, qf[0][st], acc0);
-    acc1 = mfma32(kf, qf[1][st], acc1);
+#pragma unroll
+    for (int qs = 0; qs < QS; ++qs) s[qs] = mfma32(kf, qf[qs][st], s[qs]);
   }
-  s[0] = acc0;
-  s[1] = acc1;
-  (void)KS;
 }
 
 // O^T += V^T P^T for one 32-key half tile (two MFMA k-steps of 16 keys), both query sub-tiles.
-template <int D>
-__device__ __forceinline__ void pv_half(const __bf16* Vt_half, int v_rd, const uint32_t (&pb)[2][8], f32x16 (&o)[2][D / 32]) {
-  constexpr int KS = D + 16;                        // V tile row stride
+__device__ __forceinline__ bf16x8 p_operand(const uint32_t (&pb)[8], int hf) {
+  const u32x4 pw = {pb[4 * hf + 0], pb[4 * hf + 1], pb[4 * hf + 2], pb[4 * hf + 3]};
+  return __builtin_bit_cast(bf16x8, pw);
+}
+
+template <int D, int QS>
+__device__ __forceinline__ void pv_half(const __bf16* Vt_half, int v_rd, const uint32_t (&pb)[QS][8], f32x16 (&o)[QS][D / 32]) {
+  constexpr int VS = D + 16;                        // V tile row stride
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf) {
-    const u32x4 pw0 = {pb[0][4 * hf + 0], pb[0][4 * hf + 1], pb[0][4 * hf + 2], pb[0][4 * hf + 3]};
-    const u32x4 pw1 = {pb[1][4 * hf + 0], pb[1][4 * hf + 1], pb[1][4 * hf + 2], pb[1][4 * hf + 3]};
-    const bf16x8 pf0 = __builtin_bit_cast(bf16x8, pw0);
-    const bf16x8 pf1 = __builtin_bit_cast(bf16x8, pw1);
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt) {
-      const bf16x4 v0 = lds_read_tr(&Vt_half[v_rd + (16 * hf) * KS + 32 * dt]);
-      const bf16x4 v1 = lds_read_tr(&Vt_half[v_rd + (16 * hf + 8) * KS + 32 * dt]);
+      const bf16x4 v0 = lds_read_tr(&Vt_half[v_rd + (16 * hf) * VS + 32 * dt]);
+      const bf16x4 v1 = lds_read_tr(&Vt_half[v_rd + (16 * hf + 8) * VS + 32 * dt]);
       const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-      o[0][dt] = mfma32(vf, pf0, o[0][dt]);
-      o[1][dt] = mfma32(vf, pf1, o[1][dt]);
+#pragma unroll
+      for (int qs = 0; qs < QS; ++qs) o[qs][dt] = mfma32(vf, p_operand(pb[qs], hf), o[qs][dt]);
     }
   }
 }
 
 // Row max of one half tile (per query sub-tile), in scaled log2 units.
-__device__ __forceinline__ void row_max(const f32x16 (&s)[2], float c, float (&mxc)[2]) {
+template <int QS>
+__device__ __forceinline__ void row_max(const f32x16 (&s)[QS], float c, float (&mxc)[QS]) {
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs) {
+  for (int qs = 0; qs < QS; ++qs) {
     float mx = s[qs][0];
 #pragma unroll
     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[qs][r]);
@@ -161,11 +170,14 @@ __device__ __forceinline__ void row_max(const f32x16 (&s)[2], float c, float (&m
 }
 
 // Raises the running max (and rescales l, O) only when some row outgrew it by more than kLazy.
-template <int ND>
-__device__ __forceinline__ void raise_max(const float (&mxc)[2], float (&m)[2], float (&l)[2], f32x16 (&o)[2][ND]) {
-  if (__any(mxc[0] > m[0] + kLazy || mxc[1] > m[1] + kLazy)) {
+template <int ND, int QS>
+__device__ __forceinline__ void raise_max(const float (&mxc)[QS], float (&m)[QS], float (&l)[QS], f32x16 (&o)[QS][ND]) {
+  bool grow = false;
 #pragma unroll
-    for (int qs = 0; qs < 2; ++qs) {
+  for (int qs = 0; qs < QS; ++qs) grow = grow || mxc[qs] > m[qs] + kLazy;
+  if (__any(grow)) {
+#pragma unroll
+    for (int qs = 0; qs < QS; ++qs) {
       const float mn = fmaxf(m[qs], mxc[qs]);
       const float alpha = fast_exp2(m[qs] - mn);
       m[qs] = mn;
@@ -178,17 +190,18 @@ __device__ __forceinline__ void raise_max(const float (&mxc)[2], float (&m)[2], 
   }
 }
 
-template <int ND>
-__device__ __forceinline__ void softmax_max(const f32x16 (&s)[2], float c, float (&m)[2], float (&l)[2], f32x16 (&o)[2][ND]) {
-  float mxc[2];
-  row_max(s, c, mxc);
-  raise_max<ND>(mxc, m, l, o);
+template <int ND, int QS>
+__device__ __forceinline__ void softmax_max(const f32x16 (&s)[QS], float c, float (&m)[QS], float (&l)[QS], f32x16 (&o)[QS][ND]) {
+  float mxc[QS];
+  row_max<QS>(s, c, mxc);
+  raise_max<ND, QS>(mxc, m, l, o);
 }
 
 // p = exp2(s*c - m), packed to bf16 pairs in accumulator order; row sums into l.
-__device__ __forceinline__ void softmax_exp(const f32x16 (&s)[2], float c, const float (&m)[2], float (&l)[2], uint32_t (&pb)[2][8]) {
+template <int QS>
+__device__ __forceinline__ void softmax_exp(const f32x16 (&s)[QS], float c, const float (&m)[QS], float (&l)[QS], uint32_t (&pb)[QS][8]) {
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs) {
+  for (int qs = 0; qs < QS; ++qs) {
     const float mq = m[qs];
     float ps0 = 0.f, ps1 = 0.f;
 #pragma unroll
@@ -203,9 +216,10 @@ __device__ __forceinline__ void softmax_exp(const f32x16 (&s)[2], float c, const
   }
 }
 
-__device__ __forceinline__ void mask_half(f32x16 (&s)[2], int key0, int hi, int qrow0) {
+template <int QS>
+__device__ __forceinline__ void mask_half(f32x16 (&s)[QS], int key0, int hi, int qrow0) {
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs)
+  for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
     for (int r = 0; r < 16; ++r)
       if (key0 + c_row(r, hi) > qrow0 + 32 * qs) s[qs][r] = -INFINITY;
@@ -217,8 +231,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const __bf16* base, 
   return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)bytes, 0x00020000);
 }
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 1) void attend_kernel(AttendArgs a) {
+// QS = query sub-tiles (of 32 rows) per wavefront.  QS = 2: 4 wavefronts of 64 rows, one per SIMD,
+// every LDS fragment feeds two MFMAs.  QS = 1: 8 wavefronts of 32 rows, two per SIMD, which share
+// the SIMD's issue slots (a lone wavefront issues one vector instruction every ~8 clocks, two
+// together one every ~5) at the price of one LDS fragment per MFMA.
+template <int D, int QS>
+__global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) {
+  constexpr int kThreads = 512 / QS;
+  constexpr int RW = 32 * QS;                     // query rows per wavefront
   // LDS row strides in elements.  K rows are read 16 bytes per lane by 16 lanes of consecutive
   // keys: a 16-byte pad walks them over all 64 banks.  V rows are read by the transposing load,
   // where 4 lanes cover 32 contiguous bytes of one key and the next 4 lanes the next key: a
@@ -253,20 +273,24 @@ __global__ __launch_bounds__(kThreads, 1) void attend_kernel(AttendArgs a) {
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int q0 = qt * BM;
-  const int wrow0 = q0 + 64 * wave;                      // first query row of this wavefront
-  const int half_bit = 1 << (wave >> 1);                 // which 128-row half the wavefront is in
+  const int wrow0 = q0 + RW * wave;                      // first query row of this wavefront
+  const int half_bit = 1 << ((RW * wave) / kBlock);      // which 128-row half the wavefront is in
   const float c = a.c;
   const float c_ = c;
 
   // Q^T operand fragments (two 32-row sub-tiles) stay in registers for the whole kernel
-  bf16x8 qf[2][NS];
+  bf16x8 qf[QS][NS];
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs)
+  for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(Qr, (wrow0 + 32 * qs + lo) * ROWB + 16 * hi + 32 * s, 0, 0);
       qf[qs][s] = __builtin_bit_cast(bf16x8, v);
     }
+  // Wait for Q here, on every path: otherwise the compiler's wait-count bookkeeping carries these
+  // loads as "possibly pending" into the main loop and makes every MFMA that reads a Q fragment
+  // wait for the oldest in-flight K/V prefetch as well.
+  __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0)
 
   TileGen gen;
   gen.plain = a.block_list == nullptr;
@@ -313,12 +337,15 @@ __global__ __launch_bounds__(kThreads, 1) void attend_kernel(AttendArgs a) {
   // d = 16*(lo>>4) + 4*(r&3); the group gets d = 16*(lo>>4) + (lane&15), four consecutive keys.
   const int v_rd = (4 * hi + ((lane & 15) >> 2)) * VS + 16 * (lo >> 4) + 4 * (lane & 3);
 
-  f32x16 o[2][ND];
+  f32x16 o[QS][ND];
+  float m[QS], l[QS];
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs)
+  for (int qs = 0; qs < QS; ++qs) {
+    m[qs] = kNegBig;
+    l[qs] = 0.f;
 #pragma unroll
     for (int dt = 0; dt < ND; ++dt) o[qs][dt] = f32x16{0};
-  float m[2] = {kNegBig, kNegBig}, l[2] = {0.f, 0.f};
+  }
 
   // ring slots: K(t) in kc, K(t+1) in kn, K(t+2) goes to kf; V(t) in vc, V(t+1) goes to vn
   __bf16* kc = smem;
@@ -334,8 +361,8 @@ __global__ __launch_bounds__(kThreads, 1) void attend_kernel(AttendArgs a) {
   // ---- prologue
   Tile T0 = gen.next(), T1 = gen.next(), T2 = gen.next();
   u32x4 kreg[CH], vreg[CH];
-  f32x16 sA[2], sB[2];
-  uint32_t pA[2][8], pB[2][8];
+  f32x16 sA[QS], sB[QS];
+  uint32_t pA[QS][8], pB[QS][8];
   if (T0.k0 >= 0) {
     load_tile(Kr, T0.k0, kreg);
     load_tile(Vr, T0.k0, vreg);
@@ -347,13 +374,13 @@ __global__ __launch_bounds__(kThreads, 1) void attend_kernel(AttendArgs a) {
     }
   }
   __syncthreads();
-  auto wave_active = [&](const Tile& t) -> bool { return t.k0 >= 0 && (t.use & half_bit) && t.k0 <= wrow0 + 63; };
-  if (T0.k0 >= 0) qk_half<D>(kc, k_rd, qf, sA);
+  auto wave_active = [&](const Tile& t) -> bool { return t.k0 >= 0 && (t.use & half_bit) && t.k0 <= wrow0 + RW - 1; };
+  if (T0.k0 >= 0) qk_half<D, QS>(kc, k_rd, qf, sA);
   if (T2.k0 >= 0) load_tile(Kr, T2.k0, kreg);
   if (T1.k0 >= 0) load_tile(Vr, T1.k0, vreg);
   if (wave_active(T0)) {
-    if (T0.k0 + 31 > wrow0) mask_half(sA, T0.k0, hi, wrow0 + lo);
-    softmax_max<ND>(sA, c, m, l, o);
+    if (T0.k0 + 31 > wrow0) mask_half<QS>(sA, T0.k0, hi, wrow0 + lo);
+    softmax_max<ND, QS>(sA, c, m, l, o);
   }
 
   // Invariant at the top of an iteration: sA = S^T of the first half of tile T0, already masked
@@ -404,8 +431,8 @@ __global__ __launch_bounds__(kThreads, 1) void attend_kernel(AttendArgs a) {
       for (int c = 0; c < kPF; ++c) fetch(c, kc, kn, vc);
     }
     for (; t < n_fast; ++t) {
-      float mxc[2], mx[2], ps[2];
-      f32x16 acc0, acc1;
+      float mxc[QS], mx[QS], ps0[QS], ps1[QS];
+      f32x16 acc[QS];
       const int kload = (t + 3) * BN * ROWB, vload = (t + 2) * BN * ROWB;
 #pragma unroll
       for (int c = 0; c < kChunks; ++c) {
@@ -414,16 +441,15 @@ __global__ __launch_bounds__(kThreads, 1) void attend_kernel(AttendArgs a) {
         if (c + kPF < kChunks) fetch(c + kPF, kc, kn, vc);
         else fetch(c + kPF - kChunks, kn, kf, vn);
         if (blk == 0 || blk == 2) {
-          const f32x16 (&s_in)[2] = blk == 0 ? sA : sB;
-          uint32_t (&p_out)[2][8] = blk == 0 ? pA : pB;
-          if (i == 0) { acc0 = f32x16{0}; acc1 = f32x16{0}; ps[0] = ps[1] = 0.f; }
+          const f32x16 (&s_in)[QS] = blk == 0 ? sA : sB;
+          uint32_t (&p_out)[QS][8] = blk == 0 ? pA : pB;
           constexpr int EPS = 16 / NS;
           // one MFMA, then the exponentials of one query sub-tile: the vector work runs in the
           // shadow of the MFMA that was just issued
 #pragma unroll
-          for (int qs = 0; qs < 2; ++qs) {
-            if (qs == 0) acc0 = mfma32(kfr[slot], qf[0][i], acc0);
-            else acc1 = mfma32(kfr[slot], qf[1][i], acc1);
+          for (int qs = 0; qs < QS; ++qs) {
+            if (i == 0) { acc[qs] = f32x16{0}; ps0[qs] = ps1[qs] = 0.f; }
+            acc[qs] = mfma32(kfr[slot], qf[qs][i], acc[qs]);
 #pragma unroll
             for (int e = 0; e < EPS; e += 2) {
               const int r = EPS * i + e;
@@ -438,39 +464,40 @@ __global__ __launch_bounds__(kThreads, 1) void attend_kernel(AttendArgs a) {
               const float p1 = fast_exp2(fmaf(s_in[qs][r + 1], c_, -m[qs]));
 #endif
 #if TSA_PROBE < 2
-              ps[qs] += p0 + p1;
+              ps0[qs] += p0;
+              ps1[qs] += p1;
 #endif
               p_out[qs][r >> 1] = pack_bf16(p0, p1);
             }
-            if (qs == 0) __builtin_amdgcn_sched_barrier(0);
+            if (qs + 1 < QS) __builtin_amdgcn_sched_barrier(0);
           }
           if (i == CPB - 1) {
-            f32x16 (&s_out)[2] = blk == 0 ? sB : sA;
-            s_out[0] = acc0;
-            s_out[1] = acc1;
-            l[0] += ps[0];
-            l[1] += ps[1];
+            f32x16 (&s_out)[QS] = blk == 0 ? sB : sA;
+#pragma unroll
+            for (int qs = 0; qs < QS; ++qs) {
+              s_out[qs] = acc[qs];
+              l[qs] += ps0[qs] + ps1[qs];
+            }
           }
         } else {
-          const f32x16 (&s_in)[2] = blk == 1 ? sB : sA;
-          const uint32_t (&pb)[2][8] = blk == 1 ? pA : pB;
+          const f32x16 (&s_in)[QS] = blk == 1 ? sB : sA;
+          const uint32_t (&pb)[QS][8] = blk == 1 ? pA : pB;
           const int hf = i / ND, dt = i % ND;
           constexpr int EPC = 16 / CPB;
-          if (i == 0) { mx[0] = s_in[0][0]; mx[1] = s_in[1][0]; }
-          const u32x4 pw0 = {pb[0][4 * hf + 0], pb[0][4 * hf + 1], pb[0][4 * hf + 2], pb[0][4 * hf + 3]};
-          const u32x4 pw1 = {pb[1][4 * hf + 0], pb[1][4 * hf + 1], pb[1][4 * hf + 2], pb[1][4 * hf + 3]};
           const bf16x8 vf = __builtin_shufflevector(vfl[slot], vfh[slot], 0, 1, 2, 3, 4, 5, 6, 7);
-          o[0][dt] = mfma32(vf, __builtin_bit_cast(bf16x8, pw0), o[0][dt]);
-#if TSA_PROBE < 2
 #pragma unroll
-          for (int e = 0; e < EPC; ++e) mx[0] = fmaxf(mx[0], s_in[0][EPC * i + e]);
-#endif
-          __builtin_amdgcn_sched_barrier(0);
-          o[1][dt] = mfma32(vf, __builtin_bit_cast(bf16x8, pw1), o[1][dt]);
+          for (int qs = 0; qs < QS; ++qs) {
+            if (i == 0) mx[qs] = s_in[qs][0];
+            o[qs][dt] = mfma32(vf, p_operand(pb[qs], hf), o[qs][dt]);
 #if TSA_PROBE < 2
+            if (EPC == 2) mx[qs] = __builtin_fmaxf(__builtin_fmaxf(mx[qs], s_in[qs][2 * i]), s_in[qs][2 * i + 1]);
+            else {
 #pragma unroll
-          for (int e = 0; e < EPC; ++e) mx[1] = fmaxf(mx[1], s_in[1][EPC * i + e]);
+              for (int e = 0; e < EPC; ++e) mx[qs] = fmaxf(mx[qs], s_in[qs][EPC * i + e]);
+            }
 #endif
+            if (qs + 1 < QS) __builtin_amdgcn_sched_barrier(0);
+          }
           if (blk == 3 && TSA_PROBE < 4) {                 // K(t+2) -> kf, V(t+1) -> vn, then refill the registers
             if (i < CH) {
               *(u32x4*)(&kf[lk_off + i * kRowsPerPass * KS]) = kreg[i];
@@ -482,16 +509,16 @@ __global__ __launch_bounds__(kThreads, 1) void attend_kernel(AttendArgs a) {
           }
           if (i == CPB - 1) {
 #pragma unroll
-            for (int qs = 0; qs < 2; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32)) * c_;
+            for (int qs = 0; qs < QS; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32)) * c_;
           }
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (c == 2 * CPB - 1) raise_max<ND>(mxc, m, l, o);
+        if (c == 2 * CPB - 1) raise_max<ND, QS>(mxc, m, l, o);
       }
 #if TSA_PROBE < 5
-      __syncthreads();
+      lds_barrier();
 #endif
-      raise_max<ND>(mxc, m, l, o);
+      raise_max<ND, QS>(mxc, m, l, o);
       rotate();
     }
     if (t > 0) {                                           // hand over to the general loop
@@ -503,33 +530,33 @@ __global__ __launch_bounds__(kThreads, 1) void attend_kernel(AttendArgs a) {
 
   // ---- general loop: diagonal tiles (mask, wavefronts that have nothing to do) and block lists
   while (T0.k0 >= 0) {
-    qk_half<D>(kc + 32 * KS, k_rd, qf, sB);
+    qk_half<D, QS>(kc + 32 * KS, k_rd, qf, sB);
     if (wave_active(T0)) {
-      if (T0.k0 + BN - 1 > wrow0) mask_half(sB, T0.k0 + 32, hi, wrow0 + lo);
-      softmax_exp(sA, c, m, l, pA);
-      pv_half<D>(vc, v_rd, pA, o);
-      softmax_max<ND>(sB, c, m, l, o);
-      softmax_exp(sB, c, m, l, pB);
-      pv_half<D>(vc + 32 * VS, v_rd, pB, o);
+      if (T0.k0 + BN - 1 > wrow0) mask_half<QS>(sB, T0.k0 + 32, hi, wrow0 + lo);
+      softmax_exp<QS>(sA, c, m, l, pA);
+      pv_half<D, QS>(vc, v_rd, pA, o);
+      softmax_max<ND, QS>(sB, c, m, l, o);
+      softmax_exp<QS>(sB, c, m, l, pB);
+      pv_half<D, QS>(vc + 32 * VS, v_rd, pB, o);
     }
-    if (T1.k0 >= 0) qk_half<D>(kn, k_rd, qf, sA);
+    if (T1.k0 >= 0) qk_half<D, QS>(kn, k_rd, qf, sA);
     if (wave_active(T1)) {
-      if (T1.k0 + 31 > wrow0) mask_half(sA, T1.k0, hi, wrow0 + lo);
-      softmax_max<ND>(sA, c, m, l, o);
+      if (T1.k0 + 31 > wrow0) mask_half<QS>(sA, T1.k0, hi, wrow0 + lo);
+      softmax_max<ND, QS>(sA, c, m, l, o);
     }
     if (T2.k0 >= 0) store_k(kf, kreg);
     if (T1.k0 >= 0) store_v(vn, vreg);
     const Tile T3 = gen.next();
     if (T3.k0 >= 0) load_tile(Kr, T3.k0, kreg);
     if (T2.k0 >= 0) load_tile(Vr, T2.k0, vreg);
-    __syncthreads();
+    lds_barrier();
     T0 = T1; T1 = T2; T2 = T3;
     rotate();
   }
 
   // ---- epilogue: normalise, round to bf16, store O[query][d] (a lane holds 4 consecutive d per register quad)
 #pragma unroll
-  for (int qs = 0; qs < 2; ++qs) {
+  for (int qs = 0; qs < QS; ++qs) {
     const int qrow = wrow0 + 32 * qs + lo;
     const float lt = l[qs] + __shfl_xor(l[qs], 32);
     const float inv_l = lt > 0.f ? 1.0f / lt : 0.f;
@@ -561,8 +588,8 @@ hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale
   a.nq_tiles = (Lc + BM - 1) / BM;
   a.c = scale * kLog2e;
   const unsigned grid = 8u * (unsigned)((a.BH + 7) / 8) * (unsigned)a.nq_tiles;
-  if (d == 128) attend_kernel<128><<<grid, kThreads, 0, st>>>(a);
-  else attend_kernel<64><<<grid, kThreads, 0, st>>>(a);
+  if (d == 128) attend_kernel<128, kQS><<<grid, 512 / kQS, 0, st>>>(a);
+  else attend_kernel<64, kQS><<<grid, 512 / kQS, 0, st>>>(a);
   return hipGetLastError();
 }
 
