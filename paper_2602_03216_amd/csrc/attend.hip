@@ -36,6 +36,10 @@ namespace {
 
 constexpr int BM = 256;        // query rows per workgroup
 constexpr int BN = 64;         // keys per tile
+#ifndef TSA_PF
+#define TSA_PF 3
+#define TSA_RING 4
+#endif
 #ifndef TSA_QS
 #define TSA_QS 1
 #endif
@@ -409,7 +413,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     // two transposing reads); fragments are fetched kPF chunks ahead through a small register
     // ring that runs across the blocks and across iterations, so the LDS latency is hidden even
     // though the SIMD holds a single wavefront.
-    constexpr int kPF = 3, kRing = 4, kChunks = 4 * NS;
+    constexpr int kPF = TSA_PF, kRing = TSA_RING, kChunks = 4 * NS;
     static_assert(NS == 8 || NS == 4, "chunk stream is laid out for d = 128 or 64");
     constexpr int CPB = kChunks / 4;                       // chunks per block
     bf16x8 kfr[kRing];

@@ -43,21 +43,41 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
 }
 
 // One task = one output row (b, h, t): O[b,h,t,:] = inv[t] >= 0 ? Oc[b,h,inv[t],:] : 0.
+// A thread serves kRowsPerThread rows a quarter of the tensor apart (independent loads in
+// flight); O is written once and not read again by this kernel: streaming stores.
+constexpr int kRowsPerThread = 4;
 template <int LPR>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const u32x4* __restrict__ Oc, const int32_t* __restrict__ inv, u32x4* __restrict__ O,
-    int Hq, int g_sel, int L, int k, long long n_tasks) {
+    int Hq, int g_sel, int L, int k, long long n_tasks, long long stride_tasks) {
   const long long gtid = (long long)blockIdx.x * kThreads + threadIdx.x;
-  const long long task = gtid / LPR;
+  const long long task0 = gtid / LPR;
   const int lane = (int)(gtid % LPR);
-  if (task >= n_tasks) return;
-  const int t = (int)(task % L);
-  const long long bh = task / L;
-  const long long sel_head = bh / g_sel;    // g_sel = 1 (per-head sets) or Hq/Hkv (per-group sets)
-  const int r = inv[sel_head * L + t];
-  u32x4 v = {0u, 0u, 0u, 0u};
-  if (r >= 0) v = Oc[(bh * k + r) * LPR + lane];
-  O[(bh * L + t) * LPR + lane] = v;
+  if (task0 >= stride_tasks) return;
+  int r[kRowsPerThread];
+  long long bh[kRowsPerThread];
+  int t[kRowsPerThread];
+#pragma unroll
+  for (int j = 0; j < kRowsPerThread; ++j) {
+    const long long task = task0 + j * stride_tasks;
+    r[j] = -1;
+    if (task < n_tasks) {
+      t[j] = (int)(task % L);
+      bh[j] = task / L;
+      r[j] = inv[(bh[j] / g_sel) * L + t[j]];           // g_sel = 1 (per-head sets) or Hq/Hkv (per-group sets)
+    }
+  }
+  u32x4 v[kRowsPerThread];
+#pragma unroll
+  for (int j = 0; j < kRowsPerThread; ++j) {
+    v[j] = u32x4{0u, 0u, 0u, 0u};
+    if (r[j] >= 0) v[j] = Oc[(bh[j] * k + r[j]) * LPR + lane];
+  }
+#pragma unroll
+  for (int j = 0; j < kRowsPerThread; ++j) {
+    const long long task = task0 + j * stride_tasks;
+    if (task < n_tasks) __builtin_nontemporal_store(v[j], &O[(bh[j] * L + t[j]) * LPR + lane]);
+  }
 }
 
 __device__ __forceinline__ uint32_t add_bf16_pair(uint32_t x, uint32_t o) {
@@ -114,11 +134,12 @@ hipError_t launch_compress(const Dims& dm, const void* Q, const void* K, const v
 
 hipError_t launch_decompress(const Dims& dm, const void* Oc, const int32_t* inv, int k_keep, void* O, hipStream_t st) {
   const long long n = (long long)dm.B * dm.Hq * dm.L;
+  const long long stride = (n + kRowsPerThread - 1) / kRowsPerThread;
   const int g_sel = dm.group_mode ? dm.Hq / dm.Hkv : 1;
   if (dm.d == 128)
-    decompress_kernel<16><<<blocks_for(n, 16), kThreads, 0, st>>>((const u32x4*)Oc, inv, (u32x4*)O, dm.Hq, g_sel, dm.L, k_keep, n);
+    decompress_kernel<16><<<blocks_for(stride, 16), kThreads, 0, st>>>((const u32x4*)Oc, inv, (u32x4*)O, dm.Hq, g_sel, dm.L, k_keep, n, stride);
   else
-    decompress_kernel<8><<<blocks_for(n, 8), kThreads, 0, st>>>((const u32x4*)Oc, inv, (u32x4*)O, dm.Hq, g_sel, dm.L, k_keep, n);
+    decompress_kernel<8><<<blocks_for(stride, 8), kThreads, 0, st>>>((const u32x4*)Oc, inv, (u32x4*)O, dm.Hq, g_sel, dm.L, k_keep, n, stride);
   return hipGetLastError();
 }
 

@@ -82,9 +82,13 @@ __global__ __launch_bounds__(kThreads) void score_pass1(ScoreArgs a) {
   for (int qt = 0; qt < NQT; ++qt) { m[qt] = kNegBig; z[qt] = 0.f; }
 
   const int t_begin = chunk * kChunk + wave * kKeysPerWave;
-  for (int t0 = t_begin; t0 < t_begin + kKeysPerWave && t0 < a.L; t0 += 32) {
-    bf16x8 kf[D / 16];
-    load_k_frags<D>(Kh, a.L, t0 + lo, hi, kf);
+  const int t_end = min(t_begin + kKeysPerWave, a.L);
+  bf16x8 kf[D / 16], kf_next[D / 16];
+  load_k_frags<D>(Kh, a.L, t_begin + lo, hi, kf_next);
+  for (int t0 = t_begin; t0 < t_end; t0 += 32) {
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) kf[s] = kf_next[s];
+    if (t0 + 32 < t_end) load_k_frags<D>(Kh, a.L, t0 + 32 + lo, hi, kf_next);   // in flight during the math below
     const bool need_mask = t0 + 31 > first;       // tile reaches into the window or past L
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
@@ -173,10 +177,14 @@ __global__ __launch_bounds__(kThreads) void score_pass2(ScoreArgs a) {
     for (int r = 0; r < 16; ++r) lse[qt][r] = a.lse2[bh * QP + 32 * qt + c_row(r, hi)];
 
   const int t_begin = chunk * kChunk + wave * kKeysPerWave;
-  for (int t0 = t_begin; t0 < t_begin + kKeysPerWave && t0 < a.L; t0 += 32) {
-    bf16x8 kf[D / 16];
+  const int t_end = min(t_begin + kKeysPerWave, a.L);
+  bf16x8 kf[D / 16], kf_next[D / 16];
+  load_k_frags<D>(Kh, a.L, t_begin + lo, hi, kf_next);
+  for (int t0 = t_begin; t0 < t_end; t0 += 32) {
     const int t = t0 + lo;                         // this lane's key
-    load_k_frags<D>(Kh, a.L, t, hi, kf);
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) kf[s] = kf_next[s];
+    if (t0 + 32 < t_end) load_k_frags<D>(Kh, a.L, t + 32, hi, kf_next);         // in flight during the math below
     const bool need_mask = t0 + 31 > first;
     float colsum = 0.f;
 #pragma unroll

@@ -2,10 +2,15 @@
 // Exact: the k_keep largest scores, ties to the lowest token index, emitted in ascending
 // token order together with the inverse map.  Integer work on the order-preserving uint32
 // image of the fp32 score:
-//   1. radix select (4 passes of 8 bits, histograms in LDS) finds the k-th largest key T and
-//      how many keys equal to T have to be taken;
-//   2. a stable compaction (wave ballots + prefix sums) writes idx ascending and inv.
-// One workgroup of 1024 threads per (batch, selection head).
+//   1. radix select, 4 passes of 8 bits, most significant first: every pass histograms the
+//      digit of the keys that still match the prefix found so far (LDS histograms per
+//      wavefront, one global atomic per bin and workgroup), and the next kernel derives the
+//      digit of the k-th largest key from the histogram;
+//   2. count: per wavefront segment, how many keys are above the threshold T / equal to it;
+//   3. write: prefix sums of those counts give every wavefront its output offset; a stable
+//      ballot compaction writes idx ascending and inv.
+// A head is cut into slices of 16384 tokens, one workgroup of 1024 threads per slice, so a
+// 128K-token layer with 32 heads runs 256 workgroups per kernel instead of 32.
 #include "tsa_internal.h"
 
 namespace tsa {
@@ -14,6 +19,29 @@ namespace {
 
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
+constexpr int kSlice = 16384;                 // tokens per workgroup
+constexpr int kSeg = kSlice / kWaves;         // tokens per wavefront (contiguous)
+
+struct SelState {
+  uint32_t prefix;   // digits found so far, in place
+  uint32_t krem;     // how many keys are still wanted among those that match the prefix
+};
+
+// Per selection row (batch, head or group) in the workspace:
+struct RowWs {
+  uint32_t hist[4][256];
+  SelState state[5];          // state[p]: before pass p; state[4]: (T, number of keys equal to T to take)
+  uint32_t pad[6];
+};
+
+struct SelArgs {
+  const float* scores;
+  int32_t* idx;
+  int32_t* inv;
+  RowWs* rows;
+  uint2* counts;              // [row][nslices][kWaves] (n_gt, n_eq)
+  int L, k, ff, fl, nslices;
+};
 
 // fp32 -> uint32 with the same order (-0 and +0 map to the same key)
 __device__ __forceinline__ uint32_t order_key(float f) {
@@ -27,104 +55,158 @@ __device__ __forceinline__ uint32_t key_at(const float* __restrict__ s, int t, i
   return order_key(s[t]);
 }
 
-__global__ __launch_bounds__(kThreads) void select_kernel(const float* __restrict__ scores, int32_t* __restrict__ idx,
-                                                          int32_t* __restrict__ inv, int L, int k, int ff, int fl) {
-  __shared__ uint32_t hist[kWaves][256];
-  __shared__ uint32_t total[256];
-  __shared__ uint32_t sh_prefix, sh_krem;
-  __shared__ uint32_t w_gt[kWaves], w_eq[kWaves], w_out[kWaves], w_eqb[kWaves];
-
-  const long long row = blockIdx.x;
-  const float* s = scores + row * L;
-  int32_t* out_idx = idx + row * k;
-  int32_t* out_inv = inv ? inv + row * L : nullptr;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-
-  if (tid == 0) { sh_prefix = 0u; sh_krem = (uint32_t)k; }
-  // ---- radix select, most significant digit first ----
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    for (int i = tid; i < kWaves * 256; i += kThreads) (&hist[0][0])[i] = 0u;
-    __syncthreads();
-    const uint32_t prefix = sh_prefix;
-    const uint32_t himask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
-    for (int base = 0; base < L; base += kThreads) {
-      const int t = base + tid;
-      bool valid = false;
-      uint32_t dg = 0;
-      if (t < L) {
-        const uint32_t key = key_at(s, t, L, ff, fl);
-        valid = (key & himask) == prefix;
-        dg = (key >> shift) & 255u;
-      }
-      const unsigned long long act = __ballot(valid);
-      if (act == 0ull) continue;
-      // common case in the first pass: the whole wavefront falls into one bin
-      const int leader = __ffsll((long long)act) - 1;
-      const uint32_t dg0 = __shfl(dg, leader);
-      const unsigned long long same = __ballot(valid && dg == dg0);
-      if (same == act) {
-        if (lane == leader) atomicAdd(&hist[wave][dg0], (uint32_t)__popcll(act));
-      } else if (valid) {
-        atomicAdd(&hist[wave][dg], 1u);
-      }
-    }
-    __syncthreads();
-    if (tid < 256) {
-      uint32_t c = 0;
+// Digit of the krem-th largest key among those counted in `hist`, found by the first wavefront:
+// lane l sums bins 255-4l .. 252-4l, a wave scan finds the lane where the running count from the
+// top reaches krem, the lane then walks its four bins.
+__device__ __forceinline__ SelState next_state(const uint32_t* __restrict__ hist, SelState st, int shift, int lane) {
+  uint32_t c[4];
 #pragma unroll
-      for (int w = 0; w < kWaves; ++w) c += hist[w][tid];
-      total[tid] = c;
-    }
-    __syncthreads();
-    if (tid == 0) {
-      uint32_t krem = sh_krem, above = 0;
-      int bin = 255;
-      for (; bin > 0; --bin) {
-        if (above + total[bin] >= krem) break;
-        above += total[bin];
-      }
-      sh_krem = krem - above;
-      sh_prefix = prefix | ((uint32_t)bin << shift);
-    }
-    __syncthreads();
+  for (int j = 0; j < 4; ++j) c[j] = hist[255 - 4 * lane - j];
+  const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+  uint32_t incl = mine;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t up = __shfl_up(incl, d);
+    if (lane >= d) incl += up;
   }
-  const uint32_t T = sh_prefix;          // k-th largest key
-  const uint32_t need_eq = sh_krem;      // how many keys equal to T are taken (lowest tokens first)
+  const unsigned long long reach = __ballot(incl >= st.krem);
+  const int who = reach ? __ffsll((long long)reach) - 1 : 63;
+  uint32_t above = incl - mine, bin = 255 - 4 * lane;
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    if (above + c[j] < st.krem) { above += c[j]; bin = 255 - 4 * lane - (j + 1); }
+    else break;
+  }
+  SelState out;
+  out.prefix = st.prefix | (__shfl(bin, who) << shift);
+  out.krem = st.krem - __shfl(above, who);
+  return out;
+}
 
-  // ---- stable compaction: each wavefront owns a contiguous range of tokens ----
-  const int seg = (((L + kWaves - 1) / kWaves) + 63) & ~63;
-  const int t_lo = wave * seg;
-  const int t_hi = min(L, t_lo + seg);
+__global__ void zero_hist_kernel(RowWs* rows, int n_rows) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n_rows * 1024) rows[i >> 10].hist[(i >> 8) & 3][i & 255] = 0u;
+}
+
+template <int PASS>
+__global__ __launch_bounds__(kThreads) void hist_kernel(SelArgs a) {
+  __shared__ uint32_t hist[kWaves][256];
+  __shared__ SelState sh_state;
+  const int slice = blockIdx.x;
+  const long long row = blockIdx.y;
+  RowWs* rw = a.rows + row;
+  const float* s = a.scores + row * a.L;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  constexpr int shift = 24 - 8 * PASS;
+
+  if (wave == 0) {
+    SelState st;
+    if (PASS == 0) { st.prefix = 0u; st.krem = (uint32_t)a.k; }
+    else st = next_state(rw->hist[PASS - 1], rw->state[PASS - 1], shift + 8, lane);
+    if (lane == 0) {
+      sh_state = st;
+      if (slice == 0) rw->state[PASS] = st;
+    }
+  }
+  for (int i = tid; i < kWaves * 256; i += kThreads) (&hist[0][0])[i] = 0u;
+  __syncthreads();
+  const uint32_t prefix = sh_state.prefix;
+  constexpr uint32_t himask = PASS == 0 ? 0u : (0xffffffffu << (shift + 8));
+  const int t_end = min(a.L, (slice + 1) * kSlice);
+  for (int base = slice * kSlice; base < t_end; base += kThreads) {
+    const int t = base + tid;
+    bool valid = false;
+    uint32_t dg = 0;
+    if (t < t_end) {
+      const uint32_t key = key_at(s, t, a.L, a.ff, a.fl);
+      valid = (key & himask) == prefix;
+      dg = (key >> shift) & 255u;
+    }
+    const unsigned long long act = __ballot(valid);
+    if (act == 0ull) continue;
+    // common case in the first pass: the whole wavefront falls into one bin
+    const int leader = __ffsll((long long)act) - 1;
+    const uint32_t dg0 = __shfl(dg, leader);
+    const unsigned long long same = __ballot(valid && dg == dg0);
+    if (same == act) {
+      if (lane == leader) atomicAdd(&hist[wave][dg0], (uint32_t)__popcll(act));
+    } else if (valid) {
+      atomicAdd(&hist[wave][dg], 1u);
+    }
+  }
+  __syncthreads();
+  if (tid < 256) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) c += hist[w][tid];
+    if (c) atomicAdd(&rw->hist[PASS][tid], c);
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void count_kernel(SelArgs a) {
+  __shared__ SelState sh_state;
+  const int slice = blockIdx.x;
+  const long long row = blockIdx.y;
+  RowWs* rw = a.rows + row;
+  const float* s = a.scores + row * a.L;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  if (wave == 0) {
+    const SelState st = next_state(rw->hist[3], rw->state[3], 0, lane);
+    if (lane == 0) {
+      sh_state = st;
+      if (slice == 0) rw->state[4] = st;
+    }
+  }
+  __syncthreads();
+  const uint32_t T = sh_state.prefix;
+  const int t_lo = slice * kSlice + wave * kSeg;
+  const int t_hi = min(a.L, t_lo + kSeg);
   uint32_t n_gt = 0, n_eq = 0;
   for (int base = t_lo; base < t_hi; base += 64) {
     const int t = base + lane;
-    uint32_t key = 0;
     const bool in = t < t_hi;
-    if (in) key = key_at(s, t, L, ff, fl);
+    uint32_t key = 0;
+    if (in) key = key_at(s, t, a.L, a.ff, a.fl);
     n_gt += (uint32_t)__popcll(__ballot(in && key > T));
     n_eq += (uint32_t)__popcll(__ballot(in && key == T));
   }
-  if (lane == 0) { w_gt[wave] = n_gt; w_eq[wave] = n_eq; }
-  __syncthreads();
-  if (tid == 0) {
-    uint32_t eqb = 0, outb = 0;
-    for (int w = 0; w < kWaves; ++w) {
-      w_eqb[w] = eqb;
-      w_out[w] = outb;
-      const uint32_t room = need_eq > eqb ? need_eq - eqb : 0u;
-      outb += w_gt[w] + min(room, w_eq[w]);
-      eqb += w_eq[w];
-    }
+  if (lane == 0) a.counts[(row * a.nslices + slice) * kWaves + wave] = make_uint2(n_gt, n_eq);
+}
+
+__global__ __launch_bounds__(kThreads) void write_kernel(SelArgs a) {
+  const int slice = blockIdx.x;
+  const long long row = blockIdx.y;
+  const RowWs* rw = a.rows + row;
+  const float* s = a.scores + row * a.L;
+  int32_t* out_idx = a.idx + row * a.k;
+  int32_t* out_inv = a.inv ? a.inv + row * a.L : nullptr;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const uint32_t T = rw->state[4].prefix;
+  const uint32_t need_eq = rw->state[4].krem;
+  // keys above T / equal to T in all wavefront segments before this one
+  const int my = slice * kWaves + wave;
+  const uint2* cnt = a.counts + row * a.nslices * kWaves;
+  uint32_t gt_before = 0, eq_before = 0;
+  for (int e = lane; e < my; e += 64) {
+    const uint2 c = cnt[e];
+    gt_before += c.x;
+    eq_before += c.y;
   }
-  __syncthreads();
-  uint32_t eq_run = w_eqb[wave], out_run = w_out[wave];
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    gt_before += __shfl_xor(gt_before, d);
+    eq_before += __shfl_xor(eq_before, d);
+  }
+  // ties are taken in token order until need_eq of them are used up
+  uint32_t eq_run = eq_before, out_run = gt_before + min(need_eq, eq_before);
+  const int t_lo = slice * kSlice + wave * kSeg;
+  const int t_hi = min(a.L, t_lo + kSeg);
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
   for (int base = t_lo; base < t_hi; base += 64) {
     const int t = base + lane;
     const bool in = t < t_hi;
     uint32_t key = 0;
-    if (in) key = key_at(s, t, L, ff, fl);
+    if (in) key = key_at(s, t, a.L, a.ff, a.fl);
     const bool gt = in && key > T;
     const bool eq = in && key == T;
     const unsigned long long m_eq = __ballot(eq);
@@ -150,24 +232,42 @@ __global__ void group_sum_kernel(const float* __restrict__ s, float* __restrict_
   out[i] = acc;
 }
 
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline int n_rows(const Dims& dm) { return dm.B * (dm.group_mode ? dm.Hkv : dm.Hq); }
+inline int n_slices(const Dims& dm) { return (dm.L + kSlice - 1) / kSlice; }
+
 }  // namespace
 
 size_t select_ws_bytes(const Dims& dm) {
-  if (!dm.group_mode) return 0;
-  return (((size_t)dm.B * dm.Hkv * dm.L * sizeof(float)) + 255) & ~(size_t)255;
+  size_t n = align256((size_t)n_rows(dm) * sizeof(RowWs));
+  n += align256((size_t)n_rows(dm) * n_slices(dm) * kWaves * sizeof(uint2));
+  if (dm.group_mode) n += align256((size_t)dm.B * dm.Hkv * dm.L * sizeof(float));
+  return n;
 }
 
 hipError_t launch_select(const Dims& dm, const float* scores, int k_keep, int32_t* idx, int32_t* inv,
                          void* ws, hipStream_t st) {
-  const float* src = scores;
-  int rows = dm.B * dm.Hq;
+  const int rows = n_rows(dm);
+  SelArgs a;
+  a.rows = (RowWs*)ws;
+  a.counts = (uint2*)((char*)ws + align256((size_t)rows * sizeof(RowWs)));
+  a.scores = scores;
   if (dm.group_mode) {
-    rows = dm.B * dm.Hkv;
+    float* gs = (float*)((char*)a.counts + align256((size_t)rows * n_slices(dm) * kWaves * sizeof(uint2)));
     const long long n = (long long)rows * dm.L;
-    group_sum_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(scores, (float*)ws, dm.Hq / dm.Hkv, dm.L, n);
-    src = (const float*)ws;
+    group_sum_kernel<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(scores, gs, dm.Hq / dm.Hkv, dm.L, n);
+    a.scores = gs;
   }
-  select_kernel<<<rows, kThreads, 0, st>>>(src, idx, inv, dm.L, k_keep, dm.force_first, dm.force_last);
+  a.idx = idx; a.inv = inv;
+  a.L = dm.L; a.k = k_keep; a.ff = dm.force_first; a.fl = dm.force_last; a.nslices = n_slices(dm);
+  zero_hist_kernel<<<(rows * 1024 + 255) / 256, 256, 0, st>>>(a.rows, rows);
+  const dim3 grid(a.nslices, rows);
+  hist_kernel<0><<<grid, kThreads, 0, st>>>(a);
+  hist_kernel<1><<<grid, kThreads, 0, st>>>(a);
+  hist_kernel<2><<<grid, kThreads, 0, st>>>(a);
+  hist_kernel<3><<<grid, kThreads, 0, st>>>(a);
+  count_kernel<<<grid, kThreads, 0, st>>>(a);
+  write_kernel<<<grid, kThreads, 0, st>>>(a);
   return hipGetLastError();
 }
 
