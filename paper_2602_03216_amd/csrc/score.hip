@@ -10,7 +10,9 @@
 //           queries inside the lane, one cross-half add, coalesced store of s[h, t]
 // The two orientations use the same register fragments (a lane holds 8 consecutive d-values of
 // one row), only the operand order of the MFMA is swapped, so neither pass needs a cross-lane
-// reduction longer than one step.  K fragments go straight from global memory to registers.
+// reduction longer than one step.  A workgroup serves one KV head and one chunk of keys for all
+// the query heads of the group: K tiles are staged in LDS once and every wavefront (one query
+// head each) reads its fragments from there.
 #include "tsa_internal.h"
 
 namespace tsa {
@@ -19,8 +21,8 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
-constexpr int kChunk = 1024;                 // keys per workgroup
-constexpr int kKeysPerWave = kChunk / kWaves;
+constexpr int kMinChunk = 1024;              // keys per workgroup: at least this, a multiple of kTK
+constexpr int kTK = 128;                     // keys per staged K tile
 constexpr float kNegBig = -1.0e30f;
 
 struct ScoreArgs {
@@ -29,7 +31,7 @@ struct ScoreArgs {
   float* scores;
   float2* part;       // [B*Hq][nchunks][QP] (max, sum) in the log2 domain
   float* lse2;        // [B*Hq][QP]
-  int Hq, Hkv, L, Lq, nchunks;
+  int Hq, Hkv, L, Lq, nchunks, chunk;      // chunk = keys per workgroup
   float c;            // scale * log2(e)
 };
 
@@ -50,90 +52,146 @@ __device__ __forceinline__ void load_q_frags(const ScoreArgs& a, long long bh, i
   }
 }
 
-template <int D>
-__device__ __forceinline__ void load_k_frags(const __bf16* Kh, int L, int t, int hi, bf16x8 (&kf)[D / 16]) {
-  const bool ok = t < L;
-  const __bf16* row = Kh + (long long)(ok ? t : 0) * D + 8 * hi;
-#pragma unroll
-  for (int s = 0; s < D / 16; ++s) {
-    bf16x8 v = *(const bf16x8*)(row + 16 * s);
-    if (!ok) v = bf16x8{};
-    kf[s] = v;
-  }
+// How a workgroup of (KV head, chunk of keys) spreads its four wavefronts over the g query heads
+// that share the KV head: `hpw` heads are processed at a time, one per wavefront, and the
+// remaining factor splits the keys of every staged tile.  Heads beyond hpw take further rounds.
+struct WaveRole {
+  int hpw, ksplit, hslot, kpart;
+};
+__device__ __forceinline__ WaveRole wave_role(int g, int wave) {
+  WaveRole r;
+  r.hpw = g >= 4 ? 4 : (g >= 2 ? 2 : 1);
+  r.ksplit = kWaves / r.hpw;
+  r.hslot = wave % r.hpw;
+  r.kpart = wave / r.hpw;
+  return r;
 }
+
+// K tiles of kTK keys go through LDS: coalesced 16-byte loads (a row is 16 adjacent lanes), one
+// copy per workgroup for all the heads of the group, rows padded by 16 bytes so that the
+// fragment reads (16 bytes per lane, consecutive keys) are free of bank conflicts.
+template <int D>
+struct KStage {
+  static constexpr int KS = D + 8;
+  static constexpr int CH = kTK * (D / 8) / kThreads;
+  static constexpr int kRowsPerPass = kThreads / (D / 8);
+  const __bf16* Kh;
+  int L, st_row, st_col;
+  u32x4 reg[CH];
+  __device__ __forceinline__ void load(int k0) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int key = k0 + st_row + kRowsPerPass * i;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (key < L) v = *(const u32x4*)(Kh + (long long)key * D + 8 * st_col);
+      reg[i] = v;
+    }
+  }
+  __device__ __forceinline__ void store(__bf16* dst) const {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) *(u32x4*)(&dst[(st_row + kRowsPerPass * i) * KS + 8 * st_col]) = reg[i];
+  }
+};
 
 template <int D, int NQT>
 __global__ __launch_bounds__(kThreads) void score_pass1(ScoreArgs a) {
   constexpr int QP = 32 * NQT;
+  constexpr int KS = D + 8;
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kTK * KS];
   __shared__ float2 red[kWaves][QP];
   const int chunk = blockIdx.x;
-  const long long bh = blockIdx.y;
-  const int h = (int)(bh % a.Hq);
-  const long long b = bh / a.Hq;
+  const long long bkv = blockIdx.y;
+  const int kv = (int)(bkv % a.Hkv);
+  const long long b = bkv / a.Hkv;
   const int g = a.Hq / a.Hkv;
-  const __bf16* Kh = a.K + ((b * a.Hkv + h / g) * (long long)a.L) * D;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lo = lane & 31, hi = lane >> 5;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int first = a.L - a.Lq;
+  const WaveRole role = wave_role(g, wave);
+  const int c_begin = chunk * a.chunk, c_end = min(c_begin + a.chunk, a.L);
+  const int sub_per_tile = (kTK / 32) / role.ksplit;     // 32-key sub-tiles of a staged tile per wavefront
+  KStage<D> stg;
+  stg.Kh = a.K + (bkv * (long long)a.L) * D;
+  stg.L = a.L; stg.st_row = tid / (D / 8); stg.st_col = tid % (D / 8);
+  const int k_rd = lo * KS + 8 * hi;
 
-  bf16x8 qf[NQT][D / 16];
-  load_q_frags<D, NQT>(a, bh, lo, hi, qf);
-  float m[NQT], z[NQT];
+  for (int r0 = 0; r0 < g; r0 += role.hpw) {
+    const int hh = r0 + role.hslot;
+    const bool act = hh < g;
+    const long long bh = b * a.Hq + kv * g + (act ? hh : 0);
+    bf16x8 qf[NQT][D / 16];
+    load_q_frags<D, NQT>(a, bh, lo, hi, qf);
+    float m[NQT], z[NQT];
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) { m[qt] = kNegBig; z[qt] = 0.f; }
-
-  const int t_begin = chunk * kChunk + wave * kKeysPerWave;
-  const int t_end = min(t_begin + kKeysPerWave, a.L);
-  bf16x8 kf[D / 16], kf_next[D / 16];
-  load_k_frags<D>(Kh, a.L, t_begin + lo, hi, kf_next);
-  for (int t0 = t_begin; t0 < t_end; t0 += 32) {
+    for (int qt = 0; qt < NQT; ++qt) { m[qt] = kNegBig; z[qt] = 0.f; }
+    stg.load(c_begin);
+    stg.store(Ks[0]);
+    int par = 0;
+    for (int k0 = c_begin; k0 < c_end; k0 += kTK) {
+      __syncthreads();                                 // tile k0 is staged, the other buffer is free
+      if (k0 + kTK < c_end) stg.load(k0 + kTK);        // in flight during the math below
+      if (act) {
+        for (int sb = 0; sb < sub_per_tile; ++sb) {
+          const int sub = role.kpart * sub_per_tile + sb;
+          const int t0 = k0 + 32 * sub;
+          if (t0 >= a.L) break;
+          const bool need_mask = t0 + 31 > first;      // sub-tile reaches into the window or past L
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) kf[s] = kf_next[s];
-    if (t0 + 32 < t_end) load_k_frags<D>(Kh, a.L, t0 + 32 + lo, hi, kf_next);   // in flight during the math below
-    const bool need_mask = t0 + 31 > first;       // tile reaches into the window or past L
+          for (int qt = 0; qt < NQT; ++qt) {
+            f32x16 acc = {0};
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+              const bf16x8 kf = *(const bf16x8*)(&Ks[par][32 * sub * KS + k_rd + 16 * s]);
+              acc = mfma32(kf, qf[qt][s], acc);        // rows = keys, cols = queries
+            }
+            const int qpos = first + 32 * qt + lo;     // position of this lane's query
+            if (need_mask) {
+#pragma unroll
+              for (int r = 0; r < 16; ++r) {
+                const int t = t0 + c_row(r, hi);
+                if (t > qpos || t >= a.L) acc[r] = -INFINITY;
+              }
+            }
+            float mx = acc[0];
+#pragma unroll
+            for (int r = 1; r < 16; r += 2) mx = fmaxf(fmaxf(mx, acc[r]), acc[r == 15 ? 15 : r + 1]);
+            const float mn = fmaxf(m[qt], mx * a.c);   // scale > 0: the max commutes with it
+            float sum0 = 0.f, sum1 = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+              sum0 += fast_exp2(fmaf(acc[r], a.c, -mn));
+              sum1 += fast_exp2(fmaf(acc[r + 1], a.c, -mn));
+            }
+            z[qt] = z[qt] * fast_exp2(m[qt] - mn) + sum0 + sum1;
+            m[qt] = mn;
+          }
+        }
+      }
+      if (k0 + kTK < c_end) stg.store(Ks[par ^ 1]);
+      par ^= 1;
+    }
+    // the two halves of the wavefront hold different keys of the same query
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
-      f32x16 acc = {0};
-#pragma unroll
-      for (int s = 0; s < D / 16; ++s) acc = mfma32(kf[s], qf[qt][s], acc);   // rows = keys, cols = queries
-      const int qpos = first + 32 * qt + lo;       // position of this lane's query
-      float x[16];
-      float mx = kNegBig;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = acc[r] * a.c;
-        if (need_mask) {
-          const int t = t0 + c_row(r, hi);
-          if (t > qpos || t >= a.L) v = -INFINITY;
-        }
-        x[r] = v;
-        mx = fmaxf(mx, v);
-      }
-      const float mn = fmaxf(m[qt], mx);
-      float sum = 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sum += fast_exp2(x[r] - mn);
-      z[qt] = z[qt] * fast_exp2(m[qt] - mn) + sum;
+      const float mo = __shfl_xor(m[qt], 32), zo = __shfl_xor(z[qt], 32);
+      const float mn = fmaxf(m[qt], mo);
+      z[qt] = z[qt] * fast_exp2(m[qt] - mn) + zo * fast_exp2(mo - mn);
       m[qt] = mn;
+      if (hi == 0) red[wave][32 * qt + lo] = make_float2(m[qt], z[qt]);
     }
-  }
-  // the two halves of the wavefront hold different keys of the same query
-#pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    const float mo = __shfl_xor(m[qt], 32), zo = __shfl_xor(z[qt], 32);
-    const float mn = fmaxf(m[qt], mo);
-    z[qt] = z[qt] * fast_exp2(m[qt] - mn) + zo * fast_exp2(mo - mn);
-    m[qt] = mn;
-    if (hi == 0) red[wave][32 * qt + lo] = make_float2(m[qt], z[qt]);
-  }
-  __syncthreads();
-  if (threadIdx.x < QP) {
-    float mn = kNegBig;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) mn = fmaxf(mn, red[w][threadIdx.x].x);
-    float zs = 0.f;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) zs += red[w][threadIdx.x].y * fast_exp2(red[w][threadIdx.x].x - mn);
-    a.part[(bh * a.nchunks + chunk) * QP + threadIdx.x] = make_float2(mn, zs);
+    __syncthreads();
+    // fold the key parts of every head of this round
+    for (int i = tid; i < role.hpw * QP; i += kThreads) {
+      const int slot = i / QP, q = i % QP;
+      if (r0 + slot < g) {
+        float mn = kNegBig;
+        for (int j = 0; j < role.ksplit; ++j) mn = fmaxf(mn, red[slot + role.hpw * j][q].x);
+        float zs = 0.f;
+        for (int j = 0; j < role.ksplit; ++j) zs += red[slot + role.hpw * j][q].y * fast_exp2(red[slot + role.hpw * j][q].x - mn);
+        const long long bh2 = b * a.Hq + kv * g + r0 + slot;
+        a.part[(bh2 * a.nchunks + chunk) * QP + q] = make_float2(mn, zs);
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -158,64 +216,98 @@ __global__ void score_lse(ScoreArgs a, int QP, long long n) {
 template <int D, int NQT>
 __global__ __launch_bounds__(kThreads) void score_pass2(ScoreArgs a) {
   constexpr int QP = 32 * NQT;
+  constexpr int KS = D + 8;
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kTK * KS];
   const int chunk = blockIdx.x;
-  const long long bh = blockIdx.y;
-  const int h = (int)(bh % a.Hq);
-  const long long b = bh / a.Hq;
+  const long long bkv = blockIdx.y;
+  const int kv = (int)(bkv % a.Hkv);
+  const long long b = bkv / a.Hkv;
   const int g = a.Hq / a.Hkv;
-  const __bf16* Kh = a.K + ((b * a.Hkv + h / g) * (long long)a.L) * D;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lo = lane & 31, hi = lane >> 5;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int first = a.L - a.Lq;
+  const WaveRole role = wave_role(g, wave);
+  const int c_begin = chunk * a.chunk, c_end = min(c_begin + a.chunk, a.L);
+  const int sub_per_tile = (kTK / 32) / role.ksplit;
+  KStage<D> stg;
+  stg.Kh = a.K + (bkv * (long long)a.L) * D;
+  stg.L = a.L; stg.st_row = tid / (D / 8); stg.st_col = tid % (D / 8);
+  const int k_rd = lo * KS + 8 * hi;
 
-  bf16x8 qf[NQT][D / 16];
-  load_q_frags<D, NQT>(a, bh, lo, hi, qf);
-  // log2-sum-exp of the queries this lane sees as accumulator rows
-  float lse[NQT][16];
+  for (int r0 = 0; r0 < g; r0 += role.hpw) {
+    const int hh = r0 + role.hslot;
+    const bool act = hh < g;
+    const long long bh = b * a.Hq + kv * g + (act ? hh : 0);
+    bf16x8 qf[NQT][D / 16];
+    load_q_frags<D, NQT>(a, bh, lo, hi, qf);
+    // log2-sum-exp of the queries this lane sees as accumulator rows
+    float lse[NQT][16];
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt)
+    for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) lse[qt][r] = a.lse2[bh * QP + 32 * qt + c_row(r, hi)];
-
-  const int t_begin = chunk * kChunk + wave * kKeysPerWave;
-  const int t_end = min(t_begin + kKeysPerWave, a.L);
-  bf16x8 kf[D / 16], kf_next[D / 16];
-  load_k_frags<D>(Kh, a.L, t_begin + lo, hi, kf_next);
-  for (int t0 = t_begin; t0 < t_end; t0 += 32) {
-    const int t = t0 + lo;                         // this lane's key
+      for (int r = 0; r < 16; ++r) lse[qt][r] = a.lse2[bh * QP + 32 * qt + c_row(r, hi)];
+    __syncthreads();                                   // previous round is done with both buffers
+    stg.load(c_begin);
+    stg.store(Ks[0]);
+    int par = 0;
+    for (int k0 = c_begin; k0 < c_end; k0 += kTK) {
+      __syncthreads();
+      if (k0 + kTK < c_end) stg.load(k0 + kTK);
+      if (act) {
+        for (int sb = 0; sb < sub_per_tile; ++sb) {
+          const int sub = role.kpart * sub_per_tile + sb;
+          const int t0 = k0 + 32 * sub;
+          if (t0 >= a.L) break;
+          const int t = t0 + lo;                       // this lane's key
+          const bool need_mask = t0 + 31 > first;
+          float colsum = 0.f;
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s) kf[s] = kf_next[s];
-    if (t0 + 32 < t_end) load_k_frags<D>(Kh, a.L, t + 32, hi, kf_next);         // in flight during the math below
-    const bool need_mask = t0 + 31 > first;
-    float colsum = 0.f;
+          for (int qt = 0; qt < NQT; ++qt) {
+            f32x16 acc = {0};
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-      f32x16 acc = {0};
+            for (int s = 0; s < D / 16; ++s) {
+              const bf16x8 kf = *(const bf16x8*)(&Ks[par][32 * sub * KS + k_rd + 16 * s]);
+              acc = mfma32(qf[qt][s], kf, acc);        // rows = queries, cols = keys
+            }
 #pragma unroll
-      for (int s = 0; s < D / 16; ++s) acc = mfma32(qf[qt][s], kf[s], acc);   // rows = queries, cols = keys
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = fast_exp2(acc[r] * a.c - lse[qt][r]);
-        if (need_mask) {
-          const int qpos = first + 32 * qt + c_row(r, hi);
-          if (t > qpos) p = 0.f;
+            for (int r = 0; r < 16; ++r) {
+              float p = fast_exp2(acc[r] * a.c - lse[qt][r]);
+              if (need_mask) {
+                const int qpos = first + 32 * qt + c_row(r, hi);
+                if (t > qpos) p = 0.f;
+              }
+              colsum += p;
+            }
+          }
+          colsum += __shfl_xor(colsum, 32);
+          if (hi == 0 && t < a.L) a.scores[bh * a.L + t] = colsum;
         }
-        colsum += p;
       }
+      if (k0 + kTK < c_end) stg.store(Ks[par ^ 1]);
+      par ^= 1;
     }
-    colsum += __shfl_xor(colsum, 32);
-    if (hi == 0 && t < a.L) a.scores[bh * a.L + t] = colsum;
   }
 }
 
 template <int D, int NQT>
 hipError_t run(const ScoreArgs& a, int BH, hipStream_t st) {
   constexpr int QP = 32 * NQT;
-  dim3 grid(a.nchunks, BH);
+  dim3 grid(a.nchunks, BH / (a.Hq / a.Hkv));             // one workgroup per (KV head, chunk)
   score_pass1<D, NQT><<<grid, kThreads, 0, st>>>(a);
   const long long n = (long long)BH * QP;
   score_lse<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a, QP, n);
   score_pass2<D, NQT><<<grid, kThreads, 0, st>>>(a);
   return hipGetLastError();
+}
+
+// Keys per workgroup: long enough that the start-up of a workgroup (Q fragments, first K tile)
+// is amortised, short enough for about four workgroups per CU.
+inline int chunk_for(const Dims& dm) {
+  const long long total = (long long)dm.L * dm.B * dm.Hkv;
+  long long c = total / (256 * 4);
+  c = (c + kTK - 1) / kTK * kTK;
+  if (c < kMinChunk) c = kMinChunk;
+  if (c > 8192) c = 8192;
+  return (int)c;
 }
 
 inline int nqt_for(int last_q) { return last_q <= 32 ? 1 : (last_q <= 64 ? 2 : 4); }
@@ -225,7 +317,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 size_t score_ws_bytes(const Dims& dm) {
   const int QP = 32 * nqt_for(dm.last_q);
-  const size_t nchunks = ((size_t)dm.L + kChunk - 1) / kChunk;
+  const size_t nchunks = ((size_t)dm.L + kMinChunk - 1) / kMinChunk;   // upper bound for any chunk size
   const size_t BH = (size_t)dm.B * dm.Hq;
   return align256(BH * nchunks * QP * sizeof(float2)) + align256(BH * QP * sizeof(float));
 }
@@ -236,7 +328,8 @@ hipError_t launch_score(const Dims& dm, const void* Q, const void* K, float* sco
   ScoreArgs a;
   a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.scores = scores;
   a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.L = dm.L; a.Lq = dm.last_q;
-  a.nchunks = (dm.L + kChunk - 1) / kChunk;
+  a.chunk = chunk_for(dm);
+  a.nchunks = (dm.L + a.chunk - 1) / a.chunk;
   a.c = dm.scale * kLog2e;
   const size_t BH = (size_t)dm.B * dm.Hq;
   a.part = (float2*)ws;
