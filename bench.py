@@ -174,6 +174,18 @@ def cpu_baseline(inp, k, budget_rows=2048):
     }
 
 
+def profiled_traffic():
+    """HBM bytes per launch of the headline attend dispatch, from the committed rocprofv3 counter
+    summary (FETCH_SIZE + WRITE_SIZE, scaled by the 1 GiB copy); None if it has not been profiled."""
+    path = os.path.join(ROOT, "profiles", "attend_gqa128k_tau075_hbm_traffic.txt")
+    try:
+        vals = dict(line.strip().split("=", 1) for line in open(path) if "=" in line and not line.startswith("#"))
+        return {"unit": "bytes", "fetch": float(vals["fetch_bytes_per_launch"]), "write": float(vals["write_bytes_per_launch"]),
+                "total": float(vals["fetch_bytes_per_launch"]) + float(vals["write_bytes_per_launch"])}
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -194,6 +206,15 @@ def main():
         sys.exit(2)
     tsa.load_library(build_if_missing=True)
     torch.cuda.set_device(0)
+
+    # a plain device-to-device copy of known size (1 GiB read, 1 GiB written): the reference that
+    # rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by when HBM traffic is profiled
+    src = torch.ones(1 << 28, dtype=torch.int32, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
 
     head_tau = 0.75
     taus128 = (0.75,) if args.quick else gen.CONFIGS[4]["taus"]
@@ -218,7 +239,8 @@ def main():
         "dense_ms": r128["dense_ms"],
         "roofline": {"kernel": "attend_kernel<128>", "bound": "mfma", "achieved": head["attend_tflops"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": head["attend_frac_mfma_peak"],
-                     "flops_per_launch": w["attend_flops"], "avg_launch_ms": head["attend_ms"], "traffic": None},
+                     "flops_per_launch": w["attend_flops"], "avg_launch_ms": head["attend_ms"],
+                     "traffic": profiled_traffic()},
         "paper_context": "paper reports up to x3.23 attention speedup at 128K on one NVIDIA A100 80GB (other hardware; not a target)",
         "detail": detail,
     }
