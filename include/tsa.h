@@ -79,6 +79,17 @@ size_t tsa_workspace_bytes(const tsa_desc* desc, int32_t k_keep);
 int tsa_score(const tsa_desc* desc, const void* Q, const void* K, float* scores,
               void* ws, size_t ws_bytes, void* stream);
 
+/* Dynamic Token Coverage budget -- Algorithm 1, steps "aggregate and normalize token scores across
+ * heads", "sort tokens by ascending importance" and "determine the number of sparse token":
+ * s_l[t] = sum_h scores[b,h,t] (fp32, head order), normalised by its total over t; k_sparse is the
+ * smallest k in {0..L} such that the k least important tokens carry a cumulative mass >= tau_cov;
+ * k_keep[b] = L - k_sparse, at least 1.  The result stays on the device; a caller that sizes buffers
+ * with it reads it back after synchronising the stream, then calls tsa_select with it.
+ *   scores [B,Hq,L] fp32, device;  k_keep [B] int32, device, out;  tau_cov in [0, 1]
+ *   ws: at least tsa_workspace_bytes() bytes (uses a part of it) */
+int tsa_coverage_budget(const tsa_desc* desc, const float* scores, double tau_cov, int32_t* k_keep,
+                        void* ws, size_t ws_bytes, void* stream);
+
 /* Top-k selection -- Algorithm 1, last step, S_h = TopK(s_h, k_keep): for every (b, hs)
  * the k_keep tokens of largest score, ties to the lowest token index, written in ascending
  * token order.  hs runs over Hs = Hq heads (group_mode 0) or Hs = Hkv groups (group_mode 1,

@@ -12,6 +12,8 @@ function follows one passage of the paper:
               "token-level scores per head" (Section 2.3, Dynamic Token Coverage)
   pool        the pooling(.) of the same step (the paper does not give the
               kernel; reading: average pooling, stride 1, zero padding)
+  coverage_budget  Algorithm 1, cross-head aggregation, ascending sort, cumulative-mass
+              threshold tau -> k_sparse, k_keep (the paper's dynamic budget)
   keep_count  the fixed token-sparsity ratio of the "Dynamic Sparsity vs. Fixed
               Sparsity" comparison (Table 4): a constant fraction of tokens kept
   select      Algorithm 1, "Head-wise top-k_keep token selection"
@@ -132,6 +134,35 @@ def keep_count(L: int, tau: float) -> int:
     """Fixed-ratio budget: drop floor(tau*L) tokens, keep the rest, at least one."""
     k_sparse = int(math.floor(float(tau) * L))
     return max(1, min(L, L - k_sparse))
+
+
+def coverage_budget(s: np.ndarray, tau_cov: float) -> np.ndarray:
+    """Dynamic Token Coverage budget, Algorithm 1 steps "aggregate and normalize token scores
+    across heads", "sort tokens by ascending importance" and "determine the number of sparse
+    token": s_l = sum_h s_h / sum_t sum_h s_h[t]; I = argsort(s_l); k_sparse = the smallest k in
+    {0..L} whose k least important tokens carry a cumulative mass >= tau_cov; k_keep = L - k_sparse
+    (at least 1).  s [B,Hq,L]; one k_keep per batch element, int32 [B].
+
+    The head sum is taken in float32, in head order (the precision the HIP kernel decides the
+    order of near-equal tokens in); normalisation and the cumulative mass are float64."""
+    s = np.asarray(s)
+    B, Hq, L = s.shape
+    out = np.empty(B, dtype=np.int32)
+    for b in range(B):
+        sl32 = np.zeros(L, dtype=np.float32)
+        for h in range(Hq):
+            sl32 = sl32 + s[b, h].astype(np.float32)
+        sl = sl32.astype(np.float64)
+        sl = sl / sl.sum()
+        order = np.argsort(sl, kind="stable")
+        cum = np.cumsum(sl[order])
+        if tau_cov <= 0.0:
+            k_sparse = 0
+        else:
+            reached = np.nonzero(cum >= tau_cov)[0]
+            k_sparse = int(reached[0]) + 1 if reached.size else L
+        out[b] = max(1, L - k_sparse)
+    return out
 
 
 # ----------------------------------------------------------------------------

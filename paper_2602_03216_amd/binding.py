@@ -14,7 +14,7 @@ from . import build as _build
 
 TSA_OK, TSA_ERR_ARG, TSA_ERR_UNSUPPORTED, TSA_ERR_WORKSPACE, TSA_ERR_HIP = 0, 1, 2, 3, 4
 
-EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_bytes", "tsa_score",
+EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_bytes", "tsa_score", "tsa_coverage_budget",
            "tsa_select", "tsa_compress", "tsa_attend", "tsa_decompress", "tsa_forward")
 
 
@@ -61,6 +61,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_workspace_bytes.argtypes = [dp, i32]
     lib.tsa_score.restype = ctypes.c_int
     lib.tsa_score.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+    lib.tsa_coverage_budget.restype = ctypes.c_int
+    lib.tsa_coverage_budget.argtypes = [dp, vp, ctypes.c_double, vp, vp, sz, vp]
     lib.tsa_select.restype = ctypes.c_int
     lib.tsa_select.argtypes = [dp, vp, i32, vp, vp, vp, sz, vp]
     lib.tsa_compress.restype = ctypes.c_int
@@ -119,6 +121,11 @@ def tsa_workspace_bytes(desc: tsa_desc, k_keep: int) -> int:
 def tsa_score(desc, Q, K, scores, ws):
     p, n = _ws(ws)
     _check(load_library().tsa_score(ctypes.byref(desc), _ptr(Q), _ptr(K), _ptr(scores), p, n, _stream()))
+
+
+def tsa_coverage_budget(desc, scores, tau_cov, k_keep, ws):
+    p, n = _ws(ws)
+    _check(load_library().tsa_coverage_budget(ctypes.byref(desc), _ptr(scores), float(tau_cov), _ptr(k_keep), p, n, _stream()))
 
 
 def tsa_select(desc, scores, k_keep, idx, inv, ws=None):

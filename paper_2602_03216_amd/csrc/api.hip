@@ -97,7 +97,7 @@ ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
   w.Kc = take((dm.group_mode ? BHkv : BHq) * k * row);
   w.Vc = take((dm.group_mode ? BHkv : BHq) * k * row);
   w.Oc = take(BHq * k * row);
-  w.total = off;
+  w.total = off > tsa::budget_ws_bytes(dm) ? off : tsa::budget_ws_bytes(dm);
   return w;
 }
 
@@ -133,6 +133,18 @@ int tsa_score(const tsa_desc* desc, const void* Q, const void* K, float* scores,
   if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(scores, "scores"))) return rc;
   if ((rc = check_ws(ws, ws_bytes, tsa::score_ws_bytes(dm)))) return rc;
   return hip_status(tsa::launch_score(dm, Q, K, scores, ws, (hipStream_t)stream), "tsa_score");
+}
+
+int tsa_coverage_budget(const tsa_desc* desc, const float* scores, double tau_cov, int32_t* k_keep,
+                        void* ws, size_t ws_bytes, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm))) return rc;
+  if (!(tau_cov >= 0.0) || !(tau_cov <= 1.0)) return fail(TSA_ERR_ARG, "tau_cov must lie in [0, 1]");
+  if ((rc = check_ptr(scores, "scores"))) return rc;
+  if (!k_keep || ((uintptr_t)k_keep & 3u)) return fail(TSA_ERR_ARG, "k_keep is NULL or not 4-byte aligned");
+  if ((rc = check_ws(ws, ws_bytes, tsa::budget_ws_bytes(dm)))) return rc;
+  return hip_status(tsa::launch_budget(dm, scores, tau_cov, k_keep, ws, (hipStream_t)stream), "tsa_coverage_budget");
 }
 
 int tsa_select(const tsa_desc* desc, const float* scores, int32_t k_keep,

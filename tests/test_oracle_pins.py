@@ -178,6 +178,62 @@ def test_keep_count_reproduces_table4_map_sparsity():
         assert abs(100.0 * (1 - kept_pairs / all_pairs) - printed) < 0.06
 
 
+def _budget_brute(s, tau):
+    """Pure-Python reading of Algorithm 1's budget steps on exact fractions."""
+    B, H, L = len(s), len(s[0]), len(s[0][0])
+    out = []
+    for b in range(B):
+        sl = [sum(Fraction(s[b][h][t]) for h in range(H)) for t in range(L)]
+        tot = sum(sl)
+        order = sorted(range(L), key=lambda t: (sl[t], t))
+        k_sparse, cum = None, Fraction(0)
+        if Fraction(tau) <= 0:
+            k_sparse = 0
+        else:
+            for k, t in enumerate(order, start=1):
+                cum += sl[t] / tot
+                if cum >= Fraction(tau):
+                    k_sparse = k
+                    break
+            if k_sparse is None:
+                k_sparse = L
+        out.append(max(1, L - k_sparse))
+    return out
+
+
+def test_coverage_budget_hand_cases_and_brute_force():
+    # one head, s_l = [1, 2, 5, 8] / 16: ascending cumulative mass 1/16, 3/16, 8/16, 1
+    s = np.array([[[8.0, 1.0, 5.0, 2.0]]])
+    assert orc.coverage_budget(s, 0.0)[0] == 4
+    assert orc.coverage_budget(s, 1 / 16)[0] == 3          # ">=": the first token alone reaches tau
+    assert orc.coverage_budget(s, 1.5 / 16)[0] == 2
+    assert orc.coverage_budget(s, 3 / 16)[0] == 2
+    assert orc.coverage_budget(s, 3.5 / 16)[0] == 1
+    assert orc.coverage_budget(s, 1.0)[0] == 1              # never fewer than one token
+    # uniform scores: k_sparse = ceil(tau L)
+    u = np.ones((1, 3, 64))
+    assert orc.coverage_budget(u, 4 / 64)[0] == 60 and orc.coverage_budget(u, 4.5 / 64)[0] == 59
+    # two heads: the sum over heads decides, not either head alone; dyadic values are exact in float32
+    r = _rng(31)
+    for trial in range(20):
+        B, H, L = 2, 3, int(r.integers(2, 40))
+        s = r.integers(0, 64, size=(B, H, L)).astype(np.float64) / 64.0
+        s[:, :, 0] += 1.0                                   # a positive total
+        for tau in (0.0, 1 / 128, 0.05, 0.3, 0.99):
+            assert orc.coverage_budget(s, tau).tolist() == _budget_brute(s.tolist(), tau)
+
+
+def test_coverage_budget_long_tail_prunes_the_tail():
+    # a few heavy tokens and a long tail of mass 0.4 %: tau = 0.5 % removes exactly the tail
+    L = 1000
+    s = np.full((1, 2, L), 1.0)
+    s[:, :, :4] = 250.0 * 249.0                             # heavy tokens
+    tail_mass = (L - 4) * 2.0 / s.sum()
+    k_keep = orc.coverage_budget(s, tail_mass)[0]
+    assert k_keep == 4
+    assert orc.coverage_budget(s, tail_mass * 1.0001)[0] == 3
+
+
 # ----------------------------------------------------------------------------- select
 
 def _select_brute(v, k):
