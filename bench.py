@@ -98,6 +98,8 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
             "attend": lambda: tsa.tsa_attend(desc, Qc, Kc, Vc, k, Hq, Oc),
             "decompress": lambda: tsa.tsa_decompress(desc, Oc, idx, inv, k, O=O),
         }
+        kk = torch.zeros(B, dtype=torch.int32, device=dev)
+        parts["budget"] = lambda: tsa.tsa_coverage_budget(desc, scores, 0.005, kk, ws)   # the paper's tau for this model family
         t = {}
         for name, fn in parts.items():
             fn()
@@ -108,6 +110,7 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
             "k_keep": k, "forward_ms": t_fwd, "forward_wall_ms": wall,
             "score_ms": t["score"], "select_ms": t["select"], "compress_ms": t["compress"],
             "attend_ms": t["attend"], "decompress_ms": t["decompress"],
+            "budget_ms": t["budget"], "budget_k_keep_at_tau_cov_0.005": int(kk[0].item()),
             "speedup_attend_vs_dense": t_dense / t["attend"],
             "speedup_layer_vs_dense": t_dense / t_fwd,
             "ideal_attend_speedup": (L / k) ** 2,

@@ -46,7 +46,8 @@ typedef struct tsa_desc {
   int32_t L;            /* tokens, >= 1 */
   int32_t d;            /* head dimension: 64 or 128 */
   int32_t last_q;       /* number of most recent queries used for scoring (Algorithm 1), 1..min(L,128) */
-  int32_t pool_w;       /* pooling width of Algorithm 1's pooling(.): only 1 (no pooling) is built */
+  int32_t pool_w;       /* width of Algorithm 1's pooling(.) on s_h: odd, 1 = none; average pooling, stride 1,
+                           zero padding (the paper does not give the kernel) */
   int32_t group_mode;   /* 0: every query head selects its own S_h; 1: the g heads of a KV group share
                            one set chosen from the sum of their scores */
   int32_t force_first;  /* tokens t < force_first are always kept (score treated as +inf); default 0 */
@@ -75,6 +76,7 @@ size_t tsa_workspace_bytes(const tsa_desc* desc, int32_t k_keep);
  *   Q      [B,Hq,L,d]  bf16, device (only the last last_q rows of each head are read)
  *   K      [B,Hkv,L,d] bf16, device
  *   scores [B,Hq,L]    fp32, device, fully overwritten
+ * With pool_w > 1 the column sums are then average-pooled along t (width pool_w, zero padding).
  * Arithmetic: bf16 products accumulated in fp32 (MFMA), exact two-pass softmax in fp32. */
 int tsa_score(const tsa_desc* desc, const void* Q, const void* K, float* scores,
               void* ws, size_t ws_bytes, void* stream);

@@ -31,14 +31,15 @@ int check_desc(const tsa_desc* d, tsa::Dims* out) {
   if (d->d != 64 && d->d != 128) return fail(TSA_ERR_UNSUPPORTED, "head dimension %d: only 64 and 128 are built", d->d);
   if (d->last_q < 1 || d->last_q > d->L || d->last_q > 128)
     return fail(TSA_ERR_ARG, "last_q (%d) must lie in [1, min(L, 128)]", d->last_q);
-  if (d->pool_w != 1) return fail(TSA_ERR_UNSUPPORTED, "pool_w %d: only 1 (no pooling) is built", d->pool_w);
+  if (d->pool_w < 1 || d->pool_w % 2 == 0 || d->pool_w > 1023)
+    return fail(TSA_ERR_ARG, "pool_w (%d) must be odd and lie in [1, 1023]", d->pool_w);
   if (d->group_mode != 0 && d->group_mode != 1) return fail(TSA_ERR_ARG, "group_mode must be 0 or 1");
   if (d->force_first < 0 || d->force_last < 0 || (long long)d->force_first + d->force_last > d->L)
     return fail(TSA_ERR_ARG, "force_first / force_last out of range");
   if (!(d->scale >= 0.0f) || !std::isfinite(d->scale)) return fail(TSA_ERR_ARG, "scale must be finite and >= 0");
   if ((long long)d->B * d->Hq > 65535) return fail(TSA_ERR_UNSUPPORTED, "B*Hq > 65535");
   out->B = d->B; out->Hq = d->Hq; out->Hkv = d->Hkv; out->L = d->L; out->d = d->d;
-  out->last_q = d->last_q; out->group_mode = d->group_mode;
+  out->last_q = d->last_q; out->pool_w = d->pool_w; out->group_mode = d->group_mode;
   out->force_first = d->force_first; out->force_last = d->force_last;
   out->scale = d->scale > 0.0f ? d->scale : 1.0f / std::sqrt((float)d->d);
   return TSA_OK;

@@ -32,6 +32,8 @@ struct ScoreArgs {
   float2* part;       // [B*Hq][nchunks][QP] (max, sum) in the log2 domain
   float* lse2;        // [B*Hq][QP]
   int Hq, Hkv, L, Lq, nchunks, chunk;      // chunk = keys per workgroup
+  int pool_w;
+  float* pooled;      // final output when pool_w > 1 (scores then points at a raw buffer)
   float c;            // scale * log2(e)
 };
 
@@ -288,6 +290,18 @@ __global__ __launch_bounds__(kThreads) void score_pass2(ScoreArgs a) {
   }
 }
 
+// pooling(.) of Algorithm 1, read as average pooling of odd width w, stride 1, zero padding
+__global__ void pool_kernel(const float* __restrict__ raw, float* __restrict__ out, int L, int w, long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int t = (int)(i % L);
+  const float* row = raw + (i - t);
+  const int r = w / 2;
+  float acc = 0.f;
+  for (int u = max(0, t - r); u <= min(L - 1, t + r); ++u) acc += row[u];
+  out[i] = acc / (float)w;
+}
+
 template <int D, int NQT>
 hipError_t run(const ScoreArgs& a, int BH, hipStream_t st) {
   constexpr int QP = 32 * NQT;
@@ -296,6 +310,10 @@ hipError_t run(const ScoreArgs& a, int BH, hipStream_t st) {
   const long long n = (long long)BH * QP;
   score_lse<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a, QP, n);
   score_pass2<D, NQT><<<grid, kThreads, 0, st>>>(a);
+  if (a.pool_w > 1) {
+    const long long nt = (long long)BH * a.L;
+    pool_kernel<<<(unsigned)((nt + 255) / 256), 256, 0, st>>>(a.scores, a.pooled, a.L, a.pool_w, nt);
+  }
   return hipGetLastError();
 }
 
@@ -319,7 +337,8 @@ size_t score_ws_bytes(const Dims& dm) {
   const int QP = 32 * nqt_for(dm.last_q);
   const size_t nchunks = ((size_t)dm.L + kMinChunk - 1) / kMinChunk;   // upper bound for any chunk size
   const size_t BH = (size_t)dm.B * dm.Hq;
-  return align256(BH * nchunks * QP * sizeof(float2)) + align256(BH * QP * sizeof(float));
+  return align256(BH * nchunks * QP * sizeof(float2)) + align256(BH * QP * sizeof(float)) +
+         (dm.pool_w > 1 ? align256(BH * dm.L * sizeof(float)) : 0);
 }
 
 hipError_t launch_score(const Dims& dm, const void* Q, const void* K, float* scores, void* ws, hipStream_t st) {
@@ -334,6 +353,12 @@ hipError_t launch_score(const Dims& dm, const void* Q, const void* K, float* sco
   const size_t BH = (size_t)dm.B * dm.Hq;
   a.part = (float2*)ws;
   a.lse2 = (float*)((char*)ws + align256(BH * a.nchunks * QP * sizeof(float2)));
+  a.pool_w = dm.pool_w;
+  a.pooled = nullptr;
+  if (dm.pool_w > 1) {                                   // raw column sums go to the workspace, pooled ones out
+    a.pooled = scores;
+    a.scores = (float*)((char*)a.lse2 + align256(BH * QP * sizeof(float)));
+  }
   const int bh = (int)BH;
   if (dm.d == 128) {
     if (nqt == 1) return run<128, 1>(a, bh, st);

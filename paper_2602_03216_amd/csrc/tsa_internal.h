@@ -33,7 +33,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 // Shapes every launcher gets (validated by the C-ABI layer before any launch).
 struct Dims {
-  int B, Hq, Hkv, L, d, last_q, group_mode, force_first, force_last;
+  int B, Hq, Hkv, L, d, last_q, pool_w, group_mode, force_first, force_last;
   float scale;
 };
 

@@ -71,6 +71,8 @@ def test_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert lib.tsa_decompress(dp, fake, fake, fake, 16, None, None, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_forward(dp, fake, fake, fake, 16, None, 0, 0, fake, None, None, fake, 64, None) == tsa.TSA_ERR_WORKSPACE
     assert "workspace" in tsa.tsa_last_error()
-    bad = tsa.make_desc(1, 4, 4, 1024, 64, pool_w=3)
-    assert lib.tsa_score(ctypes.byref(bad), fake, fake, fake, fake, 1 << 30, None) == tsa.TSA_ERR_UNSUPPORTED
+    bad = tsa.make_desc(1, 4, 4, 1024, 64, pool_w=4)
+    assert lib.tsa_score(ctypes.byref(bad), fake, fake, fake, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_coverage_budget(dp, fake, 1.5, fake, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_coverage_budget(dp, fake, 0.01, None, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_score(None, fake, fake, fake, fake, 1 << 30, None) == tsa.TSA_ERR_ARG

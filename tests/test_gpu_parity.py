@@ -66,6 +66,19 @@ def test_score_custom_scale_and_determinism(tsa):
     gu.assert_scores_close(s1.cpu().numpy(), orc.score(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), Lq, scale=0.05))
 
 
+@pytest.mark.parametrize("pool_w", [3, 7, 33])
+def test_score_pooled(tsa, pool_w):
+    r = _rng(50 + pool_w)
+    B, Hq, Hkv, L, d, Lq = 1, 4, 2, 1777, 128, 64
+    Qb, Kb = gu.rand_bits(r, (B, Hq, L, d)), gu.rand_bits(r, (B, Hkv, L, d), 1.3)
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq, pool_w=pool_w)
+    s = torch.full((B, Hq, L), -1.0, dtype=torch.float32, device=gu.DEV)
+    tsa.tsa_score(desc, gu.to_dev(Qb), gu.to_dev(Kb), s, _ws(tsa, desc, 1))
+    torch.cuda.synchronize()
+    want = orc.pool(orc.score(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), Lq), pool_w)
+    gu.assert_scores_close(s.cpu().numpy(), want, "pooled score")
+
+
 # ------------------------------------------------------------------ select
 
 def _run_select(tsa, scores_np, k, **kw):
