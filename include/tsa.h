@@ -149,6 +149,23 @@ int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* 
                 void* O, void* residual, int32_t* idx_out,
                 void* ws, size_t ws_bytes, void* stream);
 
+/* Sparse layer selection (Section 2.4).  Offline preprocessing in the paper; here as kernels on
+ * caller-supplied hidden states.
+ *
+ * tsa_layer_drift -- Eq. 1, Inter-Layer Representation Drift of one layer:
+ *   R = mean_t ||h_out[t] - h_in[t]||_2 / (||h_in[t]||_2 + eps)
+ *   h_in, h_out [n_tokens, width] bf16, device (the layer's input and output hidden states);
+ *   width a multiple of 8;  drift_out: one fp32 on the device;  ws: tsa_layer_drift_workspace_bytes().
+ *   fp32 sums of squares per token, fp64 mean; deterministic. */
+size_t tsa_layer_drift_workspace_bytes(int64_t n_tokens);
+int tsa_layer_drift(const void* h_in, const void* h_out, int64_t n_tokens, int32_t width, float eps,
+                    float* drift_out, void* ws, size_t ws_bytes, void* stream);
+
+/* tsa_sparse_layers -- Eq. 2, normalised drift rank and layer set, on the HOST:
+ *   rank[l] = (1/n) * #{k : R_k <= R_l};  is_sparse[l] = rank[l] <= delta  (the paper uses delta = 0.5).
+ *   drift [n_layers] fp32, host;  is_sparse [n_layers] int32, host, out (1 = apply Token Sparse Attention). */
+int tsa_sparse_layers(const float* drift, int32_t n_layers, double delta, int32_t* is_sparse);
+
 #ifdef __cplusplus
 }
 #endif

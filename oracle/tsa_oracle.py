@@ -23,6 +23,8 @@ function follows one passage of the paper:
   decompress  Section 2.2, Stage 2 (scatter into a zero-initialised tensor)
   residual_add  Section 2.2, Stage 2 last paragraph (restored output is added
               to the residual stream)
+  layer_drift, sparse_layers  Section 2.4: Eq. 1 (inter-layer representation drift) and Eq. 2
+              (normalised drift rank, layer set)
   forward     the five steps in the order of Figure 3
 
 Readings taken where the paper is silent (all repeated in the design notes):
@@ -326,6 +328,28 @@ def residual_add(x_bits: np.ndarray, Oc_bits: np.ndarray, idx: np.ndarray) -> np
             cur = bf16_to_f64(out[b, rows, h * d:(h + 1) * d])
             out[b, rows, h * d:(h + 1) * d] = f64_to_bf16(cur + bf16_to_f64(Oc_bits[b, h]))
     return out
+
+
+# ----------------------------------------------------------------------------
+# Sparse layer selection (Section 2.4)
+# ----------------------------------------------------------------------------
+
+def layer_drift(h_in: np.ndarray, h_out: np.ndarray, eps: float) -> float:
+    """Eq. 1, Inter-Layer Representation Drift: mean over tokens of
+    ||h_out[t] - h_in[t]||_2 / (||h_in[t]||_2 + eps).  h_in, h_out [n_tokens, width] float64."""
+    h_in = np.asarray(h_in, dtype=np.float64)
+    h_out = np.asarray(h_out, dtype=np.float64)
+    num = np.sqrt(((h_out - h_in) ** 2).sum(axis=1))
+    den = np.sqrt((h_in ** 2).sum(axis=1)) + eps
+    return float((num / den).mean())
+
+
+def sparse_layers(drift, delta: float = 0.5):
+    """Eq. 2: normalised drift rank R^_l = (1/N) #{k : R_k <= R_l}; the layer set {l : R^_l <= delta}.
+    Returns (rank list, list of 0/1 flags)."""
+    n = len(drift)
+    rank = [sum(1 for k in range(n) if drift[k] <= drift[l]) / n for l in range(n)]
+    return rank, [1 if r <= delta else 0 for r in rank]
 
 
 # ----------------------------------------------------------------------------

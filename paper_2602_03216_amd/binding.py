@@ -15,7 +15,8 @@ from . import build as _build
 TSA_OK, TSA_ERR_ARG, TSA_ERR_UNSUPPORTED, TSA_ERR_WORKSPACE, TSA_ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_bytes", "tsa_score", "tsa_coverage_budget",
-           "tsa_select", "tsa_compress", "tsa_attend", "tsa_decompress", "tsa_forward")
+           "tsa_select", "tsa_compress", "tsa_attend", "tsa_decompress", "tsa_forward",
+           "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers")
 
 
 class TsaError(RuntimeError):
@@ -73,6 +74,12 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_decompress.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp]
     lib.tsa_forward.restype = ctypes.c_int
     lib.tsa_forward.argtypes = [dp, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, sz, vp]
+    lib.tsa_layer_drift_workspace_bytes.restype = sz
+    lib.tsa_layer_drift_workspace_bytes.argtypes = [ctypes.c_int64]
+    lib.tsa_layer_drift.restype = ctypes.c_int
+    lib.tsa_layer_drift.argtypes = [vp, vp, ctypes.c_int64, i32, ctypes.c_float, vp, vp, sz, vp]
+    lib.tsa_sparse_layers.restype = ctypes.c_int
+    lib.tsa_sparse_layers.argtypes = [ctypes.POINTER(ctypes.c_float), i32, ctypes.c_double, ctypes.POINTER(i32)]
     _lib = lib
     return lib
 
@@ -154,6 +161,24 @@ def tsa_forward(desc, Q, K, V, k_keep, O, ws, residual=None, idx_out=None,
     _check(load_library().tsa_forward(ctypes.byref(desc), _ptr(Q), _ptr(K), _ptr(V), k_keep,
                                       _ptr(block_list), block_size, max_blocks_per_row,
                                       _ptr(O), _ptr(residual), _ptr(idx_out), p, n, _stream()))
+
+
+def tsa_layer_drift(h_in, h_out, eps, drift_out, ws=None):
+    """h_in, h_out [n_tokens, width] bf16 CUDA tensors; drift_out: 1-element fp32 CUDA tensor."""
+    n_tokens, width = h_in.shape
+    if ws is None:
+        ws = torch.empty(load_library().tsa_layer_drift_workspace_bytes(n_tokens), dtype=torch.uint8, device=h_in.device)
+    p, n = _ws(ws)
+    _check(load_library().tsa_layer_drift(_ptr(h_in), _ptr(h_out), n_tokens, width, eps, _ptr(drift_out), p, n, _stream()))
+
+
+def tsa_sparse_layers(drift, delta=0.5):
+    """Eq. 2 on the host: list of 0/1 flags, 1 = layer is eligible for Token Sparse Attention."""
+    n = len(drift)
+    arr = (ctypes.c_float * n)(*[float(v) for v in drift])
+    out = (ctypes.c_int32 * n)()
+    _check(load_library().tsa_sparse_layers(arr, n, float(delta), out))
+    return list(out)
 
 
 def alloc_workspace(desc, k_keep, device="cuda"):

@@ -240,4 +240,32 @@ int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* 
   return TSA_OK;
 }
 
+size_t tsa_layer_drift_workspace_bytes(int64_t n_tokens) {
+  if (n_tokens < 1) return 0;
+  return tsa::drift_ws_bytes(n_tokens);
+}
+
+int tsa_layer_drift(const void* h_in, const void* h_out, int64_t n_tokens, int32_t width, float eps,
+                    float* drift_out, void* ws, size_t ws_bytes, void* stream) {
+  int rc;
+  if (n_tokens < 1 || n_tokens > ((int64_t)1 << 31) * 64) return fail(TSA_ERR_ARG, "n_tokens out of range");
+  if (width < 8 || width % 8 != 0) return fail(TSA_ERR_ARG, "width (%d) must be a positive multiple of 8", width);
+  if (!(eps >= 0.0f) || !std::isfinite(eps)) return fail(TSA_ERR_ARG, "eps must be finite and >= 0");
+  if ((rc = check_ptr(h_in, "h_in")) || (rc = check_ptr(h_out, "h_out"))) return rc;
+  if (!drift_out || ((uintptr_t)drift_out & 3u)) return fail(TSA_ERR_ARG, "drift_out is NULL or not 4-byte aligned");
+  if ((rc = check_ws(ws, ws_bytes, tsa::drift_ws_bytes(n_tokens)))) return rc;
+  return hip_status(tsa::launch_drift(h_in, h_out, n_tokens, width, eps, drift_out, ws, (hipStream_t)stream), "tsa_layer_drift");
+}
+
+int tsa_sparse_layers(const float* drift, int32_t n_layers, double delta, int32_t* is_sparse) {
+  if (!drift || !is_sparse) return fail(TSA_ERR_ARG, "drift or is_sparse is NULL");
+  if (n_layers < 1) return fail(TSA_ERR_ARG, "n_layers must be >= 1");
+  for (int32_t l = 0; l < n_layers; ++l) {
+    int32_t not_above = 0;
+    for (int32_t k = 0; k < n_layers; ++k) not_above += drift[k] <= drift[l] ? 1 : 0;
+    is_sparse[l] = (double)not_above / (double)n_layers <= delta ? 1 : 0;
+  }
+  return TSA_OK;
+}
+
 }  // extern "C"

@@ -52,6 +52,11 @@ hipError_t launch_select(const Dims& dm, const float* scores, int k_keep, int32_
 size_t budget_ws_bytes(const Dims& dm);
 hipError_t launch_budget(const Dims& dm, const float* scores, double tau_cov, int32_t* k_keep, void* ws, hipStream_t st);
 
+// drift.hip
+size_t drift_ws_bytes(long long n_tokens);
+hipError_t launch_drift(const void* h_in, const void* h_out, long long n_tokens, int width, float eps, float* out,
+                        void* ws, hipStream_t st);
+
 // gather_scatter.hip
 hipError_t launch_compress(const Dims& dm, const void* Q, const void* K, const void* V, const int32_t* idx,
                            int k_keep, void* Qc, void* Kc, void* Vc, hipStream_t st);

@@ -462,3 +462,40 @@ def test_lambda_block_list_against_pair_predicate():
     # a window that covers everything is plain causal attention
     bl_all = orc.lambda_block_list(Lc, Bs, Lc + Bs, 1)
     assert np.allclose(orc.attend(Q, K, V, block_list=bl_all, block_size=Bs), orc.attend(Q, K, V), atol=1e-15)
+
+
+# ----------------------------------------------------------------------------- layer selection
+
+def test_layer_drift_closed_forms_and_brute_force():
+    r = _rng(41)
+    h = r.standard_normal((50, 24))
+    assert orc.layer_drift(h, h, 1e-6) == 0.0
+    # h_out = (1 + a) h_in: every token drifts by a ||h|| / (||h|| + eps)
+    a, eps = 0.25, 0.5
+    norms = np.sqrt((h ** 2).sum(1))
+    assert abs(orc.layer_drift(h, (1 + a) * h, eps) - np.mean(a * norms / (norms + eps))) < 1e-14
+    # a single token, 3-4-5 triangle: ||(3,4)|| / (||(6,8)|| + 0) = 1/2
+    assert orc.layer_drift(np.array([[6.0, 8.0]]), np.array([[9.0, 12.0]]), 0.0) == 0.5
+    h2 = r.standard_normal((7, 5))
+    brute = 0.0
+    for t in range(7):
+        num = math.sqrt(sum((h2[t, c] - h[t, c]) ** 2 for c in range(5)))
+        den = math.sqrt(sum(h[t, c] ** 2 for c in range(5))) + 0.1
+        brute += num / den
+    assert abs(orc.layer_drift(h[:7, :5], h2, 0.1) - brute / 7) < 1e-14
+
+
+def test_sparse_layers_rank_and_set():
+    # R = [3, 1, 2, 4]: ranks 3/4, 1/4, 2/4, 1 -> delta = 0.5 keeps layers 1 and 2
+    rank, flags = orc.sparse_layers([3.0, 1.0, 2.0, 4.0], 0.5)
+    assert rank == [0.75, 0.25, 0.5, 1.0] and flags == [0, 1, 1, 0]
+    # ties share the rank of the group's upper end (the indicator is <=)
+    rank, flags = orc.sparse_layers([1.0, 1.0, 2.0, 2.0], 0.5)
+    assert rank == [0.5, 0.5, 1.0, 1.0] and flags == [1, 1, 0, 0]
+    # the C helper of the library agrees
+    from paper_2602_03216_amd import binding as tsa
+    r = _rng(42)
+    for n in (1, 5, 32):
+        d = r.random(n).astype(np.float32).tolist()
+        for delta in (0.1, 0.5, 0.9):
+            assert tsa.tsa_sparse_layers(d, delta) == orc.sparse_layers(d, delta)[1]
