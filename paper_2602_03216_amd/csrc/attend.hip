@@ -1,27 +1,28 @@
 // Causal attention over the compacted token set (Section 2.2, Stage 1: the attention
 // operation on Q^, K^, V^ with cost O(L'^2 d)), also used unchanged as the dense baseline.
 //
-// Flash-style: one workgroup owns 256 query rows (4 wavefronts x 64 rows, one wavefront per
-// SIMD with the whole 512-entry register file), streams 64-key tiles of K and V through a
-// two-deep LDS ring, keeps the running max / sum and the output accumulator in registers
+// Flash-style: one workgroup owns 256 query rows (8 wavefronts x 32 rows, two wavefronts per
+// SIMD), streams 64-key tiles through LDS (K in a ring of three tiles, V in a ring of two, one
+// barrier per tile), keeps the running max / sum and the output accumulator in registers
 // (online softmax) and never materialises the score matrix.
 //
 // Both products run on v_mfma_f32_32x32x16_bf16 in the TRANSPOSED orientation:
-//   S^T = K Q^T   rows = keys, cols = queries  -> a lane owns ONE query per 32-row sub-tile and
-//                 32 of the 64 keys of the tile: the row max / row sum of the softmax need a
-//                 single cross-lane step (lane <-> lane^32);
+//   S^T = K Q^T   rows = keys, cols = queries  -> a lane owns ONE query of the wavefront's 32
+//                 and 32 of the 64 keys of the tile: the row max / row sum of the softmax need
+//                 a single cross-lane step (lane <-> lane^32);
 //   O^T = V^T P^T rows = d, cols = queries     -> the P^T operand is exactly what the lane
 //                 already holds (its query, eight keys per MFMA step): no shuffle and no LDS
 //                 round trip for P, and the rescale factor of O is the lane's own.
-// Every K / V fragment read from LDS feeds two MFMAs (the wavefront's two query sub-tiles):
-// LDS delivers 128 B/clk per CU, and one operand per MFMA from LDS would need all of it.
 // V stays row-major in LDS; the V^T operand comes from ds_read_b64_tr_b16, which hands each
 // lane four keys of one d-column.
-// The loop is software-pipelined: the QK product of tile t+1 is issued together with the
-// softmax arithmetic of tile t, so the matrix pipe and the vector ALU overlap inside the one
-// wavefront a SIMD holds.  The O rescale is lazy: the running max is only raised when a row's
-// new max exceeds it by more than 2^8, so most tiles skip the 128-register multiply; the
-// final division by the row sum makes the result independent of the max actually used.
+// The loop is software-pipelined: the QK product of the next half tile is issued together with
+// the softmax arithmetic of the current one, so the matrix pipe and the vector ALU overlap.
+// The O rescale is lazy: the running max is only raised when a row's new max exceeds it by
+// more than 2^8, so most tiles skip the multiply over the whole accumulator; the final
+// division by the row sum makes the result independent of the max actually used.
+// The template also holds the layout with 64 rows per wavefront (QS = 2: four wavefronts, one
+// per SIMD, every LDS fragment feeds two MFMAs); it measures slower and is not instantiated
+// by default.
 #include "tsa_internal.h"
 
 #include <climits>

@@ -54,22 +54,24 @@ def test_budget_ties_and_zeros(tsa):
 
 
 def test_budget_on_scored_workload_then_forward(tsa):
-    """Scores of the 32K grouped-KV workload -> budget at the paper's tau = 0.005 / 0.01 -> k_keep
-    equal to the oracle's on the same scores, then the layer runs with that k_keep."""
+    """Scores of the 32K grouped-KV workload (cut to 8K tokens), written by the oracle's scorer and
+    rounded to float32 -> the same array goes to the library's budget and to the oracle's, at the
+    paper's tau = 0.005 / 0.01 and a larger one; then the layer runs with that k_keep."""
     inp = gen.make_inputs(3, L=8192)
     cfg = inp.cfg
-    desc = tsa.make_desc(1, cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"])
+    L, Lq = cfg["L"], cfg["last_q"]
+    desc = tsa.make_desc(1, cfg["Hq"], cfg["Hkv"], L, cfg["d"], Lq)
+    s_np = orc.score(orc.bf16_to_f64(inp.Q[:, :, L - Lq:, :]), orc.bf16_to_f64(inp.K), Lq).astype(np.float32)
     Q, K, V = gu.to_dev(inp.Q), gu.to_dev(inp.K), gu.to_dev(inp.V)
-    ws = tsa.alloc_workspace(desc, cfg["L"], gu.DEV)
-    s = torch.empty((1, cfg["Hq"], cfg["L"]), dtype=torch.float32, device=gu.DEV)
-    tsa.tsa_score(desc, Q, K, s, ws)
+    ws = tsa.alloc_workspace(desc, L, gu.DEV)
+    s = torch.from_numpy(s_np).to(gu.DEV)
     kk = torch.zeros(1, dtype=torch.int32, device=gu.DEV)
     for tau in (0.005, 0.01, 0.05):
         tsa.tsa_coverage_budget(desc, s, tau, kk, ws)
         torch.cuda.synchronize()
         k = int(kk.item())
-        assert k == int(orc.coverage_budget(s.cpu().numpy(), tau)[0])
-        assert 1 <= k < cfg["L"]
+        assert k == int(orc.coverage_budget(s_np, tau)[0])
+        assert 1 <= k < L
         O = torch.empty_like(Q)
         idx = torch.empty((1, cfg["Hq"], k), dtype=torch.int32, device=gu.DEV)
         tsa.tsa_forward(desc, Q, K, V, k, O, tsa.alloc_workspace(desc, k, gu.DEV), idx_out=idx)
