@@ -65,7 +65,8 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
     out = {"workload": cfg["name"], "L": L, "Hq": Hq, "Hkv": Hkv, "d": d, "last_q": Lq, "per_tau": {}}
 
     # own dense attention at the same shape: the same attend kernel on the uncompressed tensors
-    dense = lambda: tsa.tsa_attend(desc, Q, K, V, L, Hkv, O)
+    ws_dense = tsa.alloc_attend_workspace(desc, L, Hkv, dev)
+    dense = lambda: tsa.tsa_attend(desc, Q, K, V, L, Hkv, O, ws_dense)
     dense()
     torch.cuda.synchronize()
     t_dense = _events_ms(dense, dense_iters, torch)
@@ -95,7 +96,7 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
             "score": lambda: tsa.tsa_score(desc, Q, K, scores, ws),
             "select": lambda: tsa.tsa_select(desc, scores, k, idx, inv, ws),
             "compress": lambda: tsa.tsa_compress(desc, Q, K, V, idx, k, Qc, Kc, Vc),
-            "attend": lambda: tsa.tsa_attend(desc, Qc, Kc, Vc, k, Hq, Oc),
+            "attend": lambda: tsa.tsa_attend(desc, Qc, Kc, Vc, k, Hq, Oc, ws),
             "decompress": lambda: tsa.tsa_decompress(desc, Oc, idx, inv, k, O=O),
         }
         kk = torch.zeros(B, dtype=torch.int32, device=dev)

@@ -4,11 +4,11 @@
  * C ABI.  Every tensor argument is a DEVICE pointer owned by the caller, 16-byte
  * aligned, contiguous row-major in the stated shape; bf16 tensors are passed as
  * `const void*` / `void*` (2 bytes per element).  The library never allocates or
- * frees device memory: scratch space comes in through the `ws` argument, sized
- * with tsa_workspace_bytes().  All work is queued asynchronously on `stream`
- * (a hipStream_t passed as void*, NULL = the default stream); no call
- * synchronises with the host, and buffers must stay valid until the stream has
- * finished the work.
+ * frees device memory: scratch space comes in through the `ws` argument (256-byte
+ * aligned), sized with tsa_workspace_bytes() or the entry point's own size query.
+ * All work is queued asynchronously on `stream` (a hipStream_t passed as void*,
+ * NULL = the default stream); no call synchronises with the host, and buffers
+ * must stay valid until the stream has finished the work.
  *
  * Every entry point returns a status code.  Arguments are validated on the
  * host before anything is launched; on error nothing has been queued and
@@ -66,8 +66,9 @@ const char* tsa_last_error(void);
  * clamped to [1, L]; returns 0 if L < 1 or tau is outside [0, 1]. */
 int32_t tsa_keep_count(int32_t L, double tau);
 
-/* Bytes of workspace that any entry point below needs for this problem and k_keep
- * (tsa_forward needs the most: scores, index sets, compacted Q/K/V and output).
+/* Bytes of workspace that tsa_score, tsa_coverage_budget, tsa_select and tsa_forward need for this
+ * problem and k_keep (tsa_forward needs the most: scores, index sets, compacted Q/K/V and output;
+ * it also covers tsa_attend on the compacted tensors).
  * Returns 0 if the descriptor or k_keep is invalid. */
 size_t tsa_workspace_bytes(const tsa_desc* desc, int32_t k_keep);
 
@@ -121,12 +122,16 @@ int tsa_compress(const tsa_desc* desc, const void* Q, const void* K, const void*
  *   compacted index space, Section 1 / Appendix "other sparse attention methods").  Entries > qb
  *   are ignored; the diagonal block is causal inside.  block_size must be 128.
  * The dense baseline is this same call with Qc=Q, Kc=K, Vc=V, Lc=L, kv_heads=Hkv.
+ *   ws: tsa_attend_workspace_bytes(desc, Lc, kv_heads) bytes (only B, Hq, d of desc are used): the
+ *   call first rewrites Vc into 64-key transposed tiles there, the layout the kernel's matrix
+ *   operands want; Vc itself is not modified.
  * Arithmetic: bf16 MFMA with fp32 accumulation, online softmax in fp32, probabilities rounded
  * to bf16 before the PV product, output rounded to bf16 (nearest even). */
+size_t tsa_attend_workspace_bytes(const tsa_desc* desc, int32_t Lc, int32_t kv_heads);
 int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void* Vc,
                int32_t Lc, int32_t kv_heads,
                const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
-               void* Oc, float* lse, void* stream);
+               void* Oc, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /* Stage 2, decompression: scatter the compressed output back to the full sequence.
  *   Oc  [B,Hq,k_keep,d] bf16;  idx [B,Hs,k_keep];  inv [B,Hs,L] (both from tsa_select)

@@ -15,7 +15,7 @@ from . import build as _build
 TSA_OK, TSA_ERR_ARG, TSA_ERR_UNSUPPORTED, TSA_ERR_WORKSPACE, TSA_ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_bytes", "tsa_score", "tsa_coverage_budget",
-           "tsa_select", "tsa_compress", "tsa_attend", "tsa_decompress", "tsa_forward",
+           "tsa_select", "tsa_compress", "tsa_attend_workspace_bytes", "tsa_attend", "tsa_decompress", "tsa_forward",
            "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers")
 
 
@@ -69,7 +69,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_compress.restype = ctypes.c_int
     lib.tsa_compress.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.tsa_attend.restype = ctypes.c_int
-    lib.tsa_attend.argtypes = [dp, vp, vp, vp, i32, i32, vp, i32, i32, vp, vp, vp]
+    lib.tsa_attend.argtypes = [dp, vp, vp, vp, i32, i32, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.tsa_attend_workspace_bytes.restype = sz
+    lib.tsa_attend_workspace_bytes.argtypes = [dp, i32, i32]
     lib.tsa_decompress.restype = ctypes.c_int
     lib.tsa_decompress.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp]
     lib.tsa_forward.restype = ctypes.c_int
@@ -145,9 +147,15 @@ def tsa_compress(desc, Q, K, V, idx, k_keep, Qc, Kc, Vc):
                                        _ptr(Qc), _ptr(Kc), _ptr(Vc), _stream()))
 
 
-def tsa_attend(desc, Qc, Kc, Vc, Lc, kv_heads, Oc, lse=None, block_list=None, block_size=0, max_blocks_per_row=0):
+def tsa_attend_workspace_bytes(desc, Lc, kv_heads):
+    return int(load_library().tsa_attend_workspace_bytes(ctypes.byref(desc), Lc, kv_heads))
+
+
+def tsa_attend(desc, Qc, Kc, Vc, Lc, kv_heads, Oc, ws, lse=None, block_list=None, block_size=0, max_blocks_per_row=0):
+    p, n = _ws(ws)
     _check(load_library().tsa_attend(ctypes.byref(desc), _ptr(Qc), _ptr(Kc), _ptr(Vc), Lc, kv_heads,
-                                     _ptr(block_list), block_size, max_blocks_per_row, _ptr(Oc), _ptr(lse), _stream()))
+                                     _ptr(block_list), block_size, max_blocks_per_row, _ptr(Oc), _ptr(lse),
+                                     p, n, _stream()))
 
 
 def tsa_decompress(desc, Oc, idx, inv, k_keep, O=None, residual=None):
@@ -179,6 +187,13 @@ def tsa_sparse_layers(drift, delta=0.5):
     out = (ctypes.c_int32 * n)()
     _check(load_library().tsa_sparse_layers(arr, n, float(delta), out))
     return list(out)
+
+
+def alloc_attend_workspace(desc, Lc, kv_heads, device="cuda"):
+    n = tsa_attend_workspace_bytes(desc, Lc, kv_heads)
+    if n == 0:
+        raise TsaError(TSA_ERR_ARG, tsa_last_error())
+    return torch.empty(n, dtype=torch.uint8, device=device)
 
 
 def alloc_workspace(desc, k_keep, device="cuda"):

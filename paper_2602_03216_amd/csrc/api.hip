@@ -79,7 +79,7 @@ int check_block_list(const int32_t* bl, int32_t block_size, int32_t max_blocks) 
 
 // Carving of the workspace used by tsa_forward (every piece 256-byte aligned).
 struct ForwardWs {
-  size_t scores, score_ws, select_ws, idx, inv, Qc, Kc, Vc, Oc, total;
+  size_t scores, score_ws, select_ws, idx, inv, Qc, Kc, Vt, Oc, total;
 };
 
 ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
@@ -96,7 +96,7 @@ ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
   w.inv = take(Hs * dm.L * sizeof(int32_t));
   w.Qc = take(BHq * k * row);
   w.Kc = take((dm.group_mode ? BHkv : BHq) * k * row);
-  w.Vc = take((dm.group_mode ? BHkv : BHq) * k * row);
+  w.Vt = take(tsa::v_tiles_bytes(dm.B, dm.group_mode ? dm.Hkv : dm.Hq, k, dm.d));
   w.Oc = take(BHq * k * row);
   w.total = off > tsa::budget_ws_bytes(dm) ? off : tsa::budget_ws_bytes(dm);
   return w;
@@ -106,7 +106,7 @@ ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
 
 extern "C" {
 
-int tsa_version(void) { return 1; }
+int tsa_version(void) { return 2; }
 
 const char* tsa_last_error(void) { return g_err; }
 
@@ -169,10 +169,17 @@ int tsa_compress(const tsa_desc* desc, const void* Q, const void* K, const void*
   return hip_status(tsa::launch_compress(dm, Q, K, V, idx, k_keep, Qc, Kc, Vc, (hipStream_t)stream), "tsa_compress");
 }
 
+size_t tsa_attend_workspace_bytes(const tsa_desc* desc, int32_t Lc, int32_t kv_heads) {
+  tsa::Dims dm;
+  if (check_desc(desc, &dm) != TSA_OK) return 0;
+  if (Lc < 1 || kv_heads < 1 || dm.Hq % kv_heads != 0) return 0;
+  return align256(tsa::v_tiles_bytes(dm.B, kv_heads, Lc, dm.d));
+}
+
 int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void* Vc,
                int32_t Lc, int32_t kv_heads,
                const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
-               void* Oc, float* lse, void* stream) {
+               void* Oc, float* lse, void* ws, size_t ws_bytes, void* stream) {
   tsa::Dims dm;
   int rc;
   if ((rc = check_desc(desc, &dm))) return rc;
@@ -184,8 +191,11 @@ int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void*
   if ((rc = check_block_list(block_list, block_size, max_blocks_per_row))) return rc;
   if ((long long)((dm.B * dm.Hq + 7) / 8) * 8 * ((Lc + 127) / 128) > 0x7fffffffLL)
     return fail(TSA_ERR_UNSUPPORTED, "grid too large");
-  return hip_status(tsa::launch_attend(dm.B, dm.Hq, kv_heads, Lc, dm.d, dm.scale, Qc, Kc, Vc, block_list,
-                                       max_blocks_per_row, Oc, lse, (hipStream_t)stream), "tsa_attend");
+  if ((rc = check_ws(ws, ws_bytes, tsa::v_tiles_bytes(dm.B, kv_heads, Lc, dm.d)))) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  if ((rc = hip_status(tsa::launch_v_tiles(dm.B, kv_heads, Lc, dm.d, Vc, ws, st), "tsa_attend(V tiles)"))) return rc;
+  return hip_status(tsa::launch_attend(dm.B, dm.Hq, kv_heads, Lc, dm.d, dm.scale, Qc, Kc, ws, block_list,
+                                       max_blocks_per_row, Oc, lse, st), "tsa_attend");
 }
 
 int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, const int32_t* inv,
@@ -222,13 +232,13 @@ int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* 
   float* scores = (float*)(base + w.scores);
   int32_t* idx = (int32_t*)(base + w.idx);
   int32_t* inv = (int32_t*)(base + w.inv);
-  void* Qc = base + w.Qc; void* Kc = base + w.Kc; void* Vc = base + w.Vc; void* Oc = base + w.Oc;
+  void* Qc = base + w.Qc; void* Kc = base + w.Kc; void* Vt = base + w.Vt; void* Oc = base + w.Oc;
   hipStream_t st = (hipStream_t)stream;
   const int kvh = dm.group_mode ? dm.Hkv : dm.Hq;
   if ((rc = hip_status(tsa::launch_score(dm, Q, K, scores, base + w.score_ws, st), "tsa_forward(score)"))) return rc;
   if ((rc = hip_status(tsa::launch_select(dm, scores, k_keep, idx, inv, base + w.select_ws, st), "tsa_forward(select)"))) return rc;
-  if ((rc = hip_status(tsa::launch_compress(dm, Q, K, V, idx, k_keep, Qc, Kc, Vc, st), "tsa_forward(compress)"))) return rc;
-  if ((rc = hip_status(tsa::launch_attend(dm.B, dm.Hq, kvh, k_keep, dm.d, dm.scale, Qc, Kc, Vc, block_list,
+  if ((rc = hip_status(tsa::launch_compress_tiled(dm, Q, K, V, idx, k_keep, Qc, Kc, Vt, st), "tsa_forward(compress)"))) return rc;
+  if ((rc = hip_status(tsa::launch_attend(dm.B, dm.Hq, kvh, k_keep, dm.d, dm.scale, Qc, Kc, Vt, block_list,
                                           max_blocks_per_row, Oc, nullptr, st), "tsa_forward(attend)"))) return rc;
   if (O && (rc = hip_status(tsa::launch_decompress(dm, Oc, inv, k_keep, O, st), "tsa_forward(decompress)"))) return rc;
   if (residual && (rc = hip_status(tsa::launch_residual(dm, Oc, idx, k_keep, residual, st), "tsa_forward(residual)"))) return rc;

@@ -36,7 +36,7 @@ namespace tsa {
 namespace {
 
 constexpr int BM = 256;        // query rows per workgroup
-constexpr int BN = 64;         // keys per tile
+constexpr int BN = kKeyTile;   // keys per tile
 #ifndef TSA_PF
 #define TSA_PF 3
 #define TSA_RING 4
@@ -52,12 +52,12 @@ constexpr float kLazy = 8.0f;  // log2 units the running max may lag behind
 struct AttendArgs {
   const __bf16* Q;
   const __bf16* K;
-  const __bf16* V;
+  const __bf16* Vt;            // tiled V^T: [B * kvh][nk_tiles][d][64]
   __bf16* O;
   float* lse;
   const int32_t* block_list;
   int max_blocks;
-  int BH, Hq, kvh, Lc, nq_tiles;
+  int BH, Hq, kvh, Lc, nq_tiles, nk_tiles;
   float c;                     // scale * log2(e)
 };
 
@@ -75,11 +75,16 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+// Row stride (elements) of a V^T tile in LDS: [d][64 keys + pad].  A fragment read takes 16 bytes
+// per lane from 16 consecutive d-rows: 144-byte rows walk those lanes over all 64 banks.
+constexpr int VS = BN + 8;
 
-__device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)p);
-}
+// Keys sit in the LDS tile in a permuted row order (bits 2 and 3 of the row swapped), so
+// that accumulator register r of lane half hi holds key 16*(r/8) + 8*hi + r%8 of its 32-key
+// half tile: the eight probabilities a lane packs for one PV step are then eight CONSECUTIVE
+// keys, and the matching V^T operand is one contiguous 16-byte read.
+__device__ __forceinline__ int k_row_perm(int lo) { return (lo & ~12) | ((lo & 4) << 1) | ((lo & 8) >> 1); }
+__device__ __forceinline__ int key_of(int r, int hi) { return 16 * (r >> 3) + 8 * hi + (r & 7); }
 
 // Key tiles a workgroup visits, in order.  `use` bit 0: the first 128 query rows of the
 // workgroup take part, bit 1: the last 128 (they can differ only under a block list).
@@ -140,6 +145,7 @@ __device__ __forceinline__ void qk_half(const __bf16* Kt_half, int k_rd, const b
 }
 
 // O^T += V^T P^T for one 32-key half tile (two MFMA k-steps of 16 keys), both query sub-tiles.
+// Vt_half points at the half's first key inside a [d][VS] tile.
 __device__ __forceinline__ bf16x8 p_operand(const uint32_t (&pb)[8], int hf) {
   const u32x4 pw = {pb[4 * hf + 0], pb[4 * hf + 1], pb[4 * hf + 2], pb[4 * hf + 3]};
   return __builtin_bit_cast(bf16x8, pw);
@@ -147,14 +153,11 @@ __device__ __forceinline__ bf16x8 p_operand(const uint32_t (&pb)[8], int hf) {
 
 template <int D, int QS>
 __device__ __forceinline__ void pv_half(const __bf16* Vt_half, int v_rd, const uint32_t (&pb)[QS][8], f32x16 (&o)[QS][D / 32]) {
-  constexpr int VS = D + 16;                        // V tile row stride
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf) {
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt) {
-      const bf16x4 v0 = lds_read_tr(&Vt_half[v_rd + (16 * hf) * VS + 32 * dt]);
-      const bf16x4 v1 = lds_read_tr(&Vt_half[v_rd + (16 * hf + 8) * VS + 32 * dt]);
-      const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+      const bf16x8 vf = *(const bf16x8*)(&Vt_half[v_rd + (32 * dt) * VS + 16 * hf]);
 #pragma unroll
       for (int qs = 0; qs < QS; ++qs) o[qs][dt] = mfma32(vf, p_operand(pb[qs], hf), o[qs][dt]);
     }
@@ -227,7 +230,7 @@ __device__ __forceinline__ void mask_half(f32x16 (&s)[QS], int key0, int hi, int
   for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
     for (int r = 0; r < 16; ++r)
-      if (key0 + c_row(r, hi) > qrow0 + 32 * qs) s[qs][r] = -INFINITY;
+      if (key0 + key_of(r, hi) > qrow0 + 32 * qs) s[qs][r] = -INFINITY;
 }
 
 // Raw buffer descriptor over one head's rows: loads past `bytes` return zero, so ragged tails
@@ -244,13 +247,10 @@ template <int D, int QS>
 __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) {
   constexpr int kThreads = 512 / QS;
   constexpr int RW = 32 * QS;                     // query rows per wavefront
-  // LDS row strides in elements.  K rows are read 16 bytes per lane by 16 lanes of consecutive
-  // keys: a 16-byte pad walks them over all 64 banks.  V rows are read by the transposing load,
-  // where 4 lanes cover 32 contiguous bytes of one key and the next 4 lanes the next key: a
-  // 32-byte pad keeps the four keys of a 16-lane group on disjoint banks.
+  // LDS row stride of a K tile in elements.  K rows are read 16 bytes per lane by 16 lanes of
+  // different keys: a 16-byte pad walks them over all 64 banks.
   constexpr int KS = D + 8;
-  constexpr int VS = D + 16;
-  constexpr int KTILE = BN * KS, VTILE = BN * VS; // elements of one staged tile
+  constexpr int KTILE = BN * KS, VTILE = D * VS;  // elements of one staged tile (K: [key][d], V: [d][key])
   constexpr int CH = BN * (D / 8) / kThreads;     // 16-byte chunks per thread per tile
   constexpr int NS = D / 16;                      // MFMA k-steps of the QK product
   constexpr int ND = D / 32;                      // d sub-tiles of the output
@@ -274,7 +274,8 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
 
   const __amdgpu_buffer_rsrc_t Qr = head_rsrc(a.Q + bh * a.Lc * D, head_bytes);
   const __amdgpu_buffer_rsrc_t Kr = head_rsrc(a.K + bkv * a.Lc * D, head_bytes);
-  const __amdgpu_buffer_rsrc_t Vr = head_rsrc(a.V + bkv * a.Lc * D, head_bytes);
+  const long long vt_bytes = (long long)a.nk_tiles * BN * ROWB;
+  const __amdgpu_buffer_rsrc_t Vr = head_rsrc(a.Vt + bkv * (vt_bytes / 2), vt_bytes);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int q0 = qt * BM;
@@ -314,18 +315,27 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     }
   }
 
-  // ---- staging: global -> registers -> LDS, 16-byte chunks, same layout for K and V.
-  // Thread chunk i covers row st_row + i * kRowsPerPass, columns 8*st_col..; the tile's first key
-  // goes into the scalar offset of the buffer load.
+  // ---- staging: global -> registers -> LDS in 16-byte chunks.  A K tile is 64 rows of the
+  // row-major tensor: thread chunk i covers row st_row + i * kRowsPerPass, columns 8*st_col.. .
+  // A V tile is one contiguous [d][64] block of the tiled V^T tensor (64 keys = 64 * ROWB bytes as
+  // well): thread chunk i is 16-byte piece tid + i * kThreads, i.e. d-row piece / 8, keys
+  // 8 * (piece % 8).. .  The tile's first key goes into the scalar offset of the buffer load.
   constexpr int kRowsPerPass = kThreads / (D / 8);
   const int st_row = tid / (D / 8), st_col = tid % (D / 8);
-  const int g_off = st_row * ROWB + 16 * st_col;                  // bytes, global side
-  const int lk_off = st_row * KS + 8 * st_col;                    // elements, LDS side (K layout)
-  const int lv_off = st_row * VS + 8 * st_col;                    // elements, LDS side (V layout)
-  auto load_tile = [&](__amdgpu_buffer_rsrc_t r, int k0, u32x4 (&reg)[CH]) {
+  const int g_off = st_row * ROWB + 16 * st_col;                  // bytes, global side (K)
+  const int lk_off = k_row_perm(st_row) * KS + 8 * st_col;        // elements, LDS side (K): permuted row order
+  const int gv_off = 16 * tid;                                    // bytes, global side (V^T)
+  const int lv_off = (tid >> 3) * VS + 8 * (tid & 7);             // elements, LDS side (V^T)
+  constexpr int kVRowsPerPass = kThreads / 8;
+  auto load_k = [&](int k0, u32x4 (&reg)[CH]) {
 #pragma unroll
     for (int i = 0; i < CH; ++i)
-      reg[i] = __builtin_amdgcn_raw_buffer_load_b128(r, g_off + i * kRowsPerPass * ROWB, k0 * ROWB, 0);
+      reg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, g_off + i * kRowsPerPass * ROWB, k0 * ROWB, 0);
+  };
+  auto load_v = [&](int k0, u32x4 (&reg)[CH]) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i)
+      reg[i] = __builtin_amdgcn_raw_buffer_load_b128(Vr, gv_off + i * kThreads * 16, k0 * ROWB, 0);
   };
   auto store_k = [&](__bf16* dst, const u32x4 (&reg)[CH]) {
 #pragma unroll
@@ -333,14 +343,15 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   };
   auto store_v = [&](__bf16* dst, const u32x4 (&reg)[CH]) {
 #pragma unroll
-    for (int i = 0; i < CH; ++i) *(u32x4*)(&dst[lv_off + i * kRowsPerPass * VS]) = reg[i];
+    for (int i = 0; i < CH; ++i) *(u32x4*)(&dst[lv_off + i * kVRowsPerPass * VS]) = reg[i];
   };
 
-  // LDS read bases.  K operand (A of S^T): row = key (lo), 8 d-values at 8*hi.
+  // LDS read bases.  K operand (A of S^T): MFMA row lo = LDS row lo = key k_row_perm(lo) of the
+  // half tile, 8 d-values at 8*hi.  (The permutation is applied when the tile is written: eight
+  // adjacent lanes must read eight adjacent LDS rows to stay free of bank conflicts.)
   const int k_rd = lo * KS + 8 * hi;
-  // V^T operand via transposing read: lane r of a 16-lane group points at key 4*hi + (r>>2),
-  // d = 16*(lo>>4) + 4*(r&3); the group gets d = 16*(lo>>4) + (lane&15), four consecutive keys.
-  const int v_rd = (4 * hi + ((lane & 15) >> 2)) * VS + 16 * (lo >> 4) + 4 * (lane & 3);
+  // V^T operand (A of O^T): row = d (lo within the 32-row d sub-tile), 8 keys at 8*hi.
+  const int v_rd = lo * VS + 8 * hi;
 
   f32x16 o[QS][ND];
   float m[QS], l[QS];
@@ -369,20 +380,20 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   f32x16 sA[QS], sB[QS];
   uint32_t pA[QS][8], pB[QS][8];
   if (T0.k0 >= 0) {
-    load_tile(Kr, T0.k0, kreg);
-    load_tile(Vr, T0.k0, vreg);
+    load_k(T0.k0, kreg);
+    load_v(T0.k0, vreg);
     store_k(kc, kreg);
     store_v(vc, vreg);
     if (T1.k0 >= 0) {
-      load_tile(Kr, T1.k0, kreg);
+      load_k(T1.k0, kreg);
       store_k(kn, kreg);
     }
   }
   __syncthreads();
   auto wave_active = [&](const Tile& t) -> bool { return t.k0 >= 0 && (t.use & half_bit) && t.k0 <= wrow0 + RW - 1; };
   if (T0.k0 >= 0) qk_half<D, QS>(kc, k_rd, qf, sA);
-  if (T2.k0 >= 0) load_tile(Kr, T2.k0, kreg);
-  if (T1.k0 >= 0) load_tile(Vr, T1.k0, vreg);
+  if (T2.k0 >= 0) load_k(T2.k0, kreg);
+  if (T1.k0 >= 0) load_v(T1.k0, vreg);
   if (wave_active(T0)) {
     if (T0.k0 + 31 > wrow0) mask_half<QS>(sA, T0.k0, hi, wrow0 + lo);
     softmax_max<ND, QS>(sA, c, m, l, o);
@@ -418,7 +429,6 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     static_assert(NS == 8 || NS == 4, "chunk stream is laid out for d = 128 or 64");
     constexpr int CPB = kChunks / 4;                       // chunks per block
     bf16x8 kfr[kRing];
-    bf16x4 vfl[kRing], vfh[kRing];
     // fragment fetch for chunk c of the iteration whose tiles sit in (kc_, kn_, vc_)
     auto fetch = [&](int c, const __bf16* kc_, const __bf16* kn_, const __bf16* vc_) {
       const int blk = c / CPB, i = c % CPB, slot = c % kRing;
@@ -426,9 +436,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
       else if (blk == 2) kfr[slot] = *(const bf16x8*)(&kn_[k_rd + 16 * i]);
       else {
         const int hf = i / ND, dt = i % ND;
-        const __bf16* vt = vc_ + (blk == 3 ? 32 * VS : 0);
-        vfl[slot] = lds_read_tr(&vt[v_rd + (16 * hf) * VS + 32 * dt]);
-        vfh[slot] = lds_read_tr(&vt[v_rd + (16 * hf + 8) * VS + 32 * dt]);
+        kfr[slot] = *(const bf16x8*)(&vc_[v_rd + (32 * dt) * VS + (blk == 3 ? 32 : 0) + 16 * hf]);
       }
     };
     if (n_fast > 0) {
@@ -489,7 +497,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
           const uint32_t (&pb)[QS][8] = blk == 1 ? pA : pB;
           const int hf = i / ND, dt = i % ND;
           constexpr int EPC = 16 / CPB;
-          const bf16x8 vf = __builtin_shufflevector(vfl[slot], vfh[slot], 0, 1, 2, 3, 4, 5, 6, 7);
+          const bf16x8 vf = kfr[slot];
 #pragma unroll
           for (int qs = 0; qs < QS; ++qs) {
             if (i == 0) mx[qs] = s_in[qs][0];
@@ -508,8 +516,8 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
               *(u32x4*)(&kf[lk_off + i * kRowsPerPass * KS]) = kreg[i];
               kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, g_off + i * kRowsPerPass * ROWB, kload, 0);
             } else if (i < 2 * CH) {
-              *(u32x4*)(&vn[lv_off + (i - CH) * kRowsPerPass * VS]) = vreg[i - CH];
-              vreg[i - CH] = __builtin_amdgcn_raw_buffer_load_b128(Vr, g_off + (i - CH) * kRowsPerPass * ROWB, vload, 0);
+              *(u32x4*)(&vn[lv_off + (i - CH) * kVRowsPerPass * VS]) = vreg[i - CH];
+              vreg[i - CH] = __builtin_amdgcn_raw_buffer_load_b128(Vr, gv_off + (i - CH) * kThreads * 16, vload, 0);
             }
           }
           if (i == CPB - 1) {
@@ -542,7 +550,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
       pv_half<D, QS>(vc, v_rd, pA, o);
       softmax_max<ND, QS>(sB, c, m, l, o);
       softmax_exp<QS>(sB, c, m, l, pB);
-      pv_half<D, QS>(vc + 32 * VS, v_rd, pB, o);
+      pv_half<D, QS>(vc + 32, v_rd, pB, o);
     }
     if (T1.k0 >= 0) qk_half<D, QS>(kn, k_rd, qf, sA);
     if (wave_active(T1)) {
@@ -552,8 +560,8 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     if (T2.k0 >= 0) store_k(kf, kreg);
     if (T1.k0 >= 0) store_v(vn, vreg);
     const Tile T3 = gen.next();
-    if (T3.k0 >= 0) load_tile(Kr, T3.k0, kreg);
-    if (T2.k0 >= 0) load_tile(Vr, T2.k0, vreg);
+    if (T3.k0 >= 0) load_k(T3.k0, kreg);
+    if (T2.k0 >= 0) load_v(T2.k0, vreg);
     lds_barrier();
     T0 = T1; T1 = T2; T2 = T3;
     rotate();
@@ -584,13 +592,14 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
 }  // namespace
 
 hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
-                         const void* Vc, const int32_t* block_list, int max_blocks_per_row, void* Oc, float* lse,
+                         const void* Vt, const int32_t* block_list, int max_blocks_per_row, void* Oc, float* lse,
                          hipStream_t st) {
   AttendArgs a;
-  a.Q = (const __bf16*)Qc; a.K = (const __bf16*)Kc; a.V = (const __bf16*)Vc; a.O = (__bf16*)Oc;
+  a.Q = (const __bf16*)Qc; a.K = (const __bf16*)Kc; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
   a.lse = lse; a.block_list = block_list; a.max_blocks = max_blocks_per_row;
   a.BH = B * Hq; a.Hq = Hq; a.kvh = kv_heads; a.Lc = Lc;
   a.nq_tiles = (Lc + BM - 1) / BM;
+  a.nk_tiles = (Lc + BN - 1) / BN;
   a.c = scale * kLog2e;
   const unsigned grid = 8u * (unsigned)((a.BH + 7) / 8) * (unsigned)a.nq_tiles;
   if (d == 128) attend_kernel<128, kQS><<<grid, 512 / kQS, 0, st>>>(a);

@@ -114,6 +114,96 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(
   *px = x;
 }
 
+// ---- tiled V^T.  One workgroup builds one tile: kKeyTile rows of V land in LDS with coalesced
+// 16-byte loads (row stride an odd number of 4-byte words, so the column reads below are free of
+// bank conflicts), then every thread assembles 16-byte pieces of a d-row from 2-byte column reads
+// and stores them coalesced.  Rows past the end are zeros.
+constexpr int kTileRowStride(int D) { return D + 2; }
+
+template <int D>
+__device__ __forceinline__ void tile_put(__bf16* tile, int r, int col, u32x4 v) {
+  uint32_t* w = (uint32_t*)(&tile[r * kTileRowStride(D) + 8 * col]);
+  w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+}
+
+template <int D>
+__device__ __forceinline__ void tile_write_transposed(const __bf16* tile, __bf16* dst) {
+  constexpr int RS = kTileRowStride(D), KC = kKeyTile / 8;
+#pragma unroll
+  for (int c = threadIdx.x; c < D * KC; c += kThreads) {
+    const int dd = c / KC, kc = c % KC;
+    const uint16_t* col = (const uint16_t*)(&tile[(8 * kc) * RS + dd]);
+    u32x4 v;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = (uint32_t)col[(2 * j) * RS] | ((uint32_t)col[(2 * j + 1) * RS] << 16);
+    *(u32x4*)(dst + dd * kKeyTile + 8 * kc) = v;
+  }
+}
+
+// V [heads][Lc][D] row-major -> V^T tiles [heads][nk_tiles][D][kKeyTile].
+template <int D>
+__global__ __launch_bounds__(kThreads) void v_tile_kernel(const u32x4* __restrict__ V, __bf16* __restrict__ Vt, int Lc, int nk_tiles) {
+  __shared__ __attribute__((aligned(16))) __bf16 tile[kKeyTile * kTileRowStride(D)];
+  constexpr int LPR = D / 8;
+  const int t = blockIdx.x;
+  const long long head = blockIdx.y;
+  const int rows = min(kKeyTile, Lc - t * kKeyTile);
+#pragma unroll
+  for (int c = threadIdx.x; c < kKeyTile * LPR; c += kThreads) {
+    const int r = c / LPR, col = c % LPR;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (r < rows) v = V[(head * Lc + (long long)t * kKeyTile + r) * LPR + col];
+    tile_put<D>(tile, r, col, v);
+  }
+  __syncthreads();
+  tile_write_transposed<D>(tile, Vt + (head * nk_tiles + t) * (long long)(D * kKeyTile));
+}
+
+// Stage 1 compression for the fused layer: one workgroup = kKeyTile consecutive compacted rows of one
+// query head: Q and K rows are copied as in compress_kernel, V rows go through LDS into the
+// tile of V^T the attention kernel will read.  With per-group sets only the first query head
+// of a group moves K and V.
+struct CompressTiledArgs {
+  const u32x4* Q; const u32x4* K; const u32x4* V; const int32_t* idx;
+  u32x4* Qc; u32x4* Kc; __bf16* Vt;
+  int Hq, Hkv, L, k, group_mode, nk_tiles;
+};
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void compress_tiled_kernel(CompressTiledArgs a) {
+  __shared__ __attribute__((aligned(16))) __bf16 tile[kKeyTile * kTileRowStride(D)];
+  __shared__ int tok[kKeyTile];
+  constexpr int LPR = D / 8;
+  const int t = blockIdx.x;
+  const long long bh = blockIdx.y;
+  const int h = (int)(bh % a.Hq);
+  const long long b = bh / a.Hq;
+  const int g = a.Hq / a.Hkv;
+  const long long bkv = b * a.Hkv + h / g;
+  const long long sel_head = a.group_mode ? bkv : bh;
+  const bool kv_owner = a.group_mode == 0 || h % g == 0;
+  const int r0 = t * kKeyTile;
+  if (threadIdx.x < kKeyTile) tok[threadIdx.x] = r0 + (int)threadIdx.x < a.k ? a.idx[sel_head * a.k + r0 + threadIdx.x] : -1;
+  __syncthreads();
+#pragma unroll
+  for (int c = threadIdx.x; c < kKeyTile * LPR; c += kThreads) {
+    const int r = c / LPR, col = c % LPR;
+    const int tk = tok[r];
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (tk >= 0) {
+      a.Qc[(bh * a.k + r0 + r) * LPR + col] = a.Q[(bh * a.L + tk) * LPR + col];
+      if (kv_owner) {
+        a.Kc[(sel_head * a.k + r0 + r) * LPR + col] = a.K[(bkv * a.L + tk) * LPR + col];
+        v = a.V[(bkv * a.L + tk) * LPR + col];
+      }
+    }
+    tile_put<D>(tile, r, col, v);
+  }
+  if (!kv_owner) return;                     // the same for every thread of the workgroup
+  __syncthreads();
+  tile_write_transposed<D>(tile, a.Vt + (sel_head * a.nk_tiles + t) * (long long)(D * kKeyTile));
+}
+
 inline unsigned blocks_for(long long n_tasks, int lpr) {
   return (unsigned)((n_tasks * lpr + kThreads - 1) / kThreads);
 }
@@ -129,6 +219,27 @@ hipError_t launch_compress(const Dims& dm, const void* Q, const void* K, const v
     compress_kernel<16><<<blocks_for(n, 16), kThreads, 0, st>>>(q, k, v, idx, qc, kc, vc, dm.Hq, dm.Hkv, dm.L, k_keep, dm.group_mode, n);
   else
     compress_kernel<8><<<blocks_for(n, 8), kThreads, 0, st>>>(q, k, v, idx, qc, kc, vc, dm.Hq, dm.Hkv, dm.L, k_keep, dm.group_mode, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_v_tiles(int B, int kv_heads, int Lc, int d, const void* V, void* Vt, hipStream_t st) {
+  const int nk_tiles = (Lc + kKeyTile - 1) / kKeyTile;
+  const dim3 grid((unsigned)nk_tiles, (unsigned)(B * kv_heads));
+  if (d == 128) v_tile_kernel<128><<<grid, kThreads, 0, st>>>((const u32x4*)V, (__bf16*)Vt, Lc, nk_tiles);
+  else v_tile_kernel<64><<<grid, kThreads, 0, st>>>((const u32x4*)V, (__bf16*)Vt, Lc, nk_tiles);
+  return hipGetLastError();
+}
+
+hipError_t launch_compress_tiled(const Dims& dm, const void* Q, const void* K, const void* V, const int32_t* idx,
+                                 int k_keep, void* Qc, void* Kc, void* Vt, hipStream_t st) {
+  CompressTiledArgs a;
+  a.Q = (const u32x4*)Q; a.K = (const u32x4*)K; a.V = (const u32x4*)V; a.idx = idx;
+  a.Qc = (u32x4*)Qc; a.Kc = (u32x4*)Kc; a.Vt = (__bf16*)Vt;
+  a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.L = dm.L; a.k = k_keep; a.group_mode = dm.group_mode;
+  a.nk_tiles = (k_keep + kKeyTile - 1) / kKeyTile;
+  const dim3 grid((unsigned)a.nk_tiles, (unsigned)(dm.B * dm.Hq));
+  if (dm.d == 128) compress_tiled_kernel<128><<<grid, kThreads, 0, st>>>(a);
+  else compress_tiled_kernel<64><<<grid, kThreads, 0, st>>>(a);
   return hipGetLastError();
 }
 

@@ -63,9 +63,22 @@ hipError_t launch_compress(const Dims& dm, const void* Q, const void* K, const v
 hipError_t launch_decompress(const Dims& dm, const void* Oc, const int32_t* inv, int k_keep, void* O, hipStream_t st);
 hipError_t launch_residual(const Dims& dm, const void* Oc, const int32_t* idx, int k_keep, void* residual, hipStream_t st);
 
+// The attention kernel reads V as tiled V^T: [B*kv_heads][ceil(Lc/kKeyTile)][d][kKeyTile] bf16 (one d-row
+// of a tile = kKeyTile consecutive keys = 128 contiguous bytes), keys past Lc zero.
+constexpr int kKeyTile = 64;
+inline size_t v_tiles_bytes(int B, int kv_heads, int Lc, int d) {
+  return (size_t)B * kv_heads * ((Lc + kKeyTile - 1) / kKeyTile) * kKeyTile * d * 2;
+}
+
+// gather_scatter.hip (continued): row-major V -> tiled V^T; and Stage 1 compression writing
+// Qc, Kc row-major and V directly as tiled V^T (the form tsa_forward uses).
+hipError_t launch_v_tiles(int B, int kv_heads, int Lc, int d, const void* V, void* Vt, hipStream_t st);
+hipError_t launch_compress_tiled(const Dims& dm, const void* Q, const void* K, const void* V, const int32_t* idx,
+                                 int k_keep, void* Qc, void* Kc, void* Vt, hipStream_t st);
+
 // attend.hip
 hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
-                         const void* Vc, const int32_t* block_list, int max_blocks_per_row, void* Oc, float* lse,
+                         const void* Vt, const int32_t* block_list, int max_blocks_per_row, void* Oc, float* lse,
                          hipStream_t st);
 
 }  // namespace tsa

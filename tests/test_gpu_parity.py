@@ -198,8 +198,10 @@ def test_attend_matches_oracle(tsa, B, Hq, Hk, Lc, d):
     desc = tsa.make_desc(B, Hq, Hk, max(Lc, 1), d, 1)
     O = torch.full((B, Hq, Lc, d), 9.0, dtype=torch.bfloat16, device=gu.DEV)
     lse = torch.zeros((B, Hq, Lc), dtype=torch.float32, device=gu.DEV)
-    tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, Hk, O, lse)
+    Vd = gu.to_dev(Vb)
+    tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), Vd, Lc, Hk, O, tsa.alloc_attend_workspace(desc, Lc, Hk, gu.DEV), lse)
     torch.cuda.synchronize()
+    assert np.array_equal(gu.from_dev(Vd), Vb)                 # the caller's V is left alone
     want, wlse = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), return_lse=True)
     gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend")
     assert np.abs(lse.cpu().numpy() - wlse).max() < 2e-3
@@ -215,7 +217,7 @@ def test_attend_large_logits_and_scale(tsa):
     Qb, Kb, Vb = gu.rand_bits(r, (B, H, Lc, d), 4.0), gu.rand_bits(r, (B, H, Lc, d), 4.0), gu.rand_bits(r, (B, H, Lc, d))
     desc = tsa.make_desc(B, H, H, Lc, d, 1, scale=0.2)        # logits of several hundred: the running max must hold
     O = torch.empty((B, H, Lc, d), dtype=torch.bfloat16, device=gu.DEV)
-    tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, H, O)
+    tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, H, O, tsa.alloc_attend_workspace(desc, Lc, H, gu.DEV))
     want = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), scale=0.2)
     gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(large logits)")
 
@@ -228,7 +230,7 @@ def test_attend_block_list(tsa, Lc, window):
     bl = orc.lambda_block_list(Lc, Bs, window, 1)
     desc = tsa.make_desc(B, Hq, Hk, Lc, d, 1)
     O = torch.empty((B, Hq, Lc, d), dtype=torch.bfloat16, device=gu.DEV)
-    tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, Hk, O,
+    tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, Hk, O, tsa.alloc_attend_workspace(desc, Lc, Hk, gu.DEV),
                    block_list=torch.from_numpy(bl).to(gu.DEV), block_size=Bs, max_blocks_per_row=bl.shape[1])
     want = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), block_list=bl, block_size=Bs)
     gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(block list)")
