@@ -178,6 +178,26 @@ def cpu_baseline(inp, k, budget_rows=2048):
     }
 
 
+def mfma_calibration(tsa, torch, K):
+    """Rate and shader clock of a bare bf16 MFMA loop (no memory traffic) on zeros and on the
+    workload's own key values: what the matrix cores sustain on this data under the chip's power
+    limit, next to the published peak that the roofline fraction is priced against."""
+    dev = K.device
+    blocks, iters = 2 * torch.cuda.get_device_properties(dev).multi_processor_count, 20000
+    sink = torch.empty(blocks * 256, dtype=torch.float32, device=dev)
+    clocks = torch.zeros(2, dtype=torch.int64, device=dev)
+    out = {}
+    for name, operands in (("zeros", torch.zeros(1 << 15, dtype=torch.bfloat16, device=dev)),
+                           ("workload_keys", K.reshape(-1)[: 1 << 15].contiguous())):
+        fn = lambda: tsa.tsa_mfma_probe(operands, iters, blocks, sink, clocks)
+        flops, khz = fn()
+        torch.cuda.synchronize()
+        ms = _events_ms(fn, 5, torch)
+        cyc, ticks = [int(v) for v in clocks.cpu()]
+        out[name] = {"tflops": flops / ms / 1e9, "shader_clock_mhz": cyc / (ticks / (khz * 1e3)) / 1e6}
+    return out
+
+
 def profiled_traffic():
     """HBM bytes per launch of the headline attend dispatch, from the committed rocprofv3 counter
     summary (FETCH_SIZE + WRITE_SIZE, scaled by the 1 GiB copy); None if it has not been profiled."""
@@ -229,6 +249,8 @@ def main():
         detail["gqa_32k"] = r32
     head = r128["per_tau"][str(head_tau)]
     cfg = inp128.cfg
+    import numpy as np
+    calib = mfma_calibration(tsa, torch, torch.from_numpy(inp128.K.view(np.int16)).to("cuda:0").view(torch.bfloat16))
     w = algorithmic_work(cfg, head["k_keep"])
     line = {
         "metric": "prefill_attention_ms_per_layer", "value": head["forward_ms"], "unit": "ms",
@@ -244,7 +266,9 @@ def main():
         "roofline": {"kernel": "attend_kernel<128>", "bound": "mfma", "achieved": head["attend_tflops"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": head["attend_frac_mfma_peak"],
                      "flops_per_launch": w["attend_flops"], "avg_launch_ms": head["attend_ms"],
-                     "traffic": profiled_traffic()},
+                     "traffic": profiled_traffic(),
+                     "bare_mfma_loop": calib,
+                     "frac_of_bare_mfma_loop_on_workload_values": head["attend_tflops"] / calib["workload_keys"]["tflops"]},
         "paper_context": "paper reports up to x3.23 attention speedup at 128K on one NVIDIA A100 80GB (other hardware; not a target)",
         "detail": detail,
     }

@@ -171,6 +171,19 @@ int tsa_layer_drift(const void* h_in, const void* h_out, int64_t n_tokens, int32
  *   drift [n_layers] fp32, host;  is_sparse [n_layers] int32, host, out (1 = apply Token Sparse Attention). */
 int tsa_sparse_layers(const float* drift, int32_t n_layers, double delta, int32_t* is_sparse);
 
+/* Roofline calibration (not a step of the method): runs a bare loop of 8 * iters bf16 MFMAs
+ * (32x32x16) per wavefront, 4 wavefronts per workgroup, `blocks` workgroups, with operand values taken
+ * from `operands`, and records the shader clock it ran at.  The sustained matrix rate of the chip
+ * depends on the operand values (clock under power limit); a benchmark uses this to report the
+ * rate a pure MFMA stream reaches on the workload's own data beside the published peak.
+ *   operands: device, at least 64 KiB of bf16 values;  sink: device, blocks * 256 fp32 (scratch output)
+ *   clocks: device int64[2], out: {shader-clock cycles, wall-clock ticks} of workgroup 0's loop
+ *   flops (host, out, may be NULL): floating-point operations of the whole launch
+ *   wall_clock_khz (host, out, may be NULL): rate of the wall clock in kHz
+ * The caller times the launch (events on `stream`) and divides. */
+int tsa_mfma_probe(const void* operands, int32_t iters, int32_t blocks, float* sink, int64_t* clocks,
+                   double* flops, int32_t* wall_clock_khz, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

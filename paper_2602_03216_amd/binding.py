@@ -16,7 +16,7 @@ TSA_OK, TSA_ERR_ARG, TSA_ERR_UNSUPPORTED, TSA_ERR_WORKSPACE, TSA_ERR_HIP = 0, 1,
 
 EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_bytes", "tsa_score", "tsa_coverage_budget",
            "tsa_select", "tsa_compress", "tsa_attend_workspace_bytes", "tsa_attend", "tsa_decompress", "tsa_forward",
-           "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers")
+           "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe")
 
 
 class TsaError(RuntimeError):
@@ -70,6 +70,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_compress.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.tsa_attend.restype = ctypes.c_int
     lib.tsa_attend.argtypes = [dp, vp, vp, vp, i32, i32, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.tsa_mfma_probe.restype = ctypes.c_int
+    lib.tsa_mfma_probe.argtypes = [vp, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32), vp]
     lib.tsa_attend_workspace_bytes.restype = sz
     lib.tsa_attend_workspace_bytes.argtypes = [dp, i32, i32]
     lib.tsa_decompress.restype = ctypes.c_int
@@ -187,6 +189,14 @@ def tsa_sparse_layers(drift, delta=0.5):
     out = (ctypes.c_int32 * n)()
     _check(load_library().tsa_sparse_layers(arr, n, float(delta), out))
     return list(out)
+
+
+def tsa_mfma_probe(operands, iters, blocks, sink, clocks):
+    """Queues the bare MFMA loop; returns (flops of the launch, wall clock rate in kHz)."""
+    flops, khz = ctypes.c_double(0.0), ctypes.c_int32(0)
+    _check(load_library().tsa_mfma_probe(_ptr(operands), iters, blocks, _ptr(sink), _ptr(clocks),
+                                         ctypes.byref(flops), ctypes.byref(khz), _stream()))
+    return flops.value, khz.value
 
 
 def alloc_attend_workspace(desc, Lc, kv_heads, device="cuda"):

@@ -10,7 +10,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libtsa.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "budget.hip", "drift.hip", "gather_scatter.hip", "attend.hip"]
+SOURCES = ["api.hip", "score.hip", "select.hip", "budget.hip", "drift.hip", "gather_scatter.hip", "probe.hip", "attend.hip"]
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 instructions.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -278,4 +278,19 @@ int tsa_sparse_layers(const float* drift, int32_t n_layers, double delta, int32_
   return TSA_OK;
 }
 
+int tsa_mfma_probe(const void* operands, int32_t iters, int32_t blocks, float* sink, int64_t* clocks,
+                   double* flops, int32_t* wall_clock_khz, void* stream) {
+  int rc;
+  if ((rc = check_ptr(operands, "operands")) || (rc = check_ptr(sink, "sink")) || (rc = check_ptr(clocks, "clocks"))) return rc;
+  if (iters < 1 || iters > (1 << 24) || blocks < 1 || blocks > 65536) return fail(TSA_ERR_ARG, "iters or blocks out of range");
+  if (flops) *flops = (double)blocks * 4.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
+  if (wall_clock_khz) {
+    int dev = 0, khz = 0;
+    if ((rc = hip_status(hipGetDevice(&dev), "hipGetDevice"))) return rc;
+    if ((rc = hip_status(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev), "wall clock rate"))) return rc;
+    *wall_clock_khz = khz;
+  }
+  return hip_status(tsa::launch_mfma_probe(operands, iters, blocks, sink, (long long*)clocks, (hipStream_t)stream), "tsa_mfma_probe");
+}
+
 }  // extern "C"

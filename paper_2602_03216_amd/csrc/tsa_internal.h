@@ -81,4 +81,7 @@ hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale
                          const void* Vt, const int32_t* block_list, int max_blocks_per_row, void* Oc, float* lse,
                          hipStream_t st);
 
+// probe.hip: bare MFMA loop, 8 * iters MFMAs per wavefront, 4 wavefronts per workgroup
+hipError_t launch_mfma_probe(const void* operands, int iters, int blocks, float* sink, long long* clocks, hipStream_t st);
+
 }  // namespace tsa
