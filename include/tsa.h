@@ -67,8 +67,8 @@ const char* tsa_last_error(void);
 int32_t tsa_keep_count(int32_t L, double tau);
 
 /* Bytes of workspace that tsa_score, tsa_coverage_budget, tsa_select and tsa_forward need for this
- * problem and k_keep (tsa_forward needs the most: scores, index sets, compacted Q/K/V and output;
- * it also covers tsa_attend on the compacted tensors).
+ * problem and k_keep (tsa_forward needs the most: scores, index sets, the gathered V and the
+ * compacted output; it also covers tsa_attend on the compacted tensors).
  * Returns 0 if the descriptor or k_keep is invalid. */
 size_t tsa_workspace_bytes(const tsa_desc* desc, int32_t k_keep);
 
@@ -145,7 +145,9 @@ int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, con
                    int32_t k_keep, void* O, void* residual, void* stream);
 
 /* The whole layer on one stream, no host synchronisation:
- * score -> select -> compress -> attend -> decompress (Figure 3 of the paper).
+ * score -> select -> compress -> attend -> decompress (Figure 3 of the paper).  Same results as the
+ * five calls in a row; inside, the gather of Q and K rows happens in the attention kernel's loads
+ * and the scatter (with the zero rows) in its epilogue, so the compacted Q, K, O never touch HBM.
  *   Q [B,Hq,L,d], K, V [B,Hkv,L,d] bf16;  O [B,Hq,L,d] bf16 out (or NULL when only residual is wanted)
  *   idx_out [B,Hs,k_keep] int32 out or NULL;  residual as in tsa_decompress or NULL
  *   block_list / block_size / max_blocks_per_row as in tsa_attend (NULL, 0, 0 for plain causal) */

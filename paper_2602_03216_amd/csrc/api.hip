@@ -79,7 +79,7 @@ int check_block_list(const int32_t* bl, int32_t block_size, int32_t max_blocks) 
 
 // Carving of the workspace used by tsa_forward (every piece 256-byte aligned).
 struct ForwardWs {
-  size_t scores, score_ws, select_ws, idx, inv, Qc, Kc, Vt, Oc, total;
+  size_t scores, score_ws, select_ws, idx, inv, Vt, Oc, total;
 };
 
 ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
@@ -94,8 +94,6 @@ ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
   w.select_ws = take(tsa::select_ws_bytes(dm));
   w.idx = take(Hs * k * sizeof(int32_t));
   w.inv = take(Hs * dm.L * sizeof(int32_t));
-  w.Qc = take(BHq * k * row);
-  w.Kc = take((dm.group_mode ? BHkv : BHq) * k * row);
   w.Vt = take(tsa::v_tiles_bytes(dm.B, dm.group_mode ? dm.Hkv : dm.Hq, k, dm.d));
   w.Oc = take(BHq * k * row);
   w.total = off > tsa::budget_ws_bytes(dm) ? off : tsa::budget_ws_bytes(dm);
@@ -232,15 +230,17 @@ int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* 
   float* scores = (float*)(base + w.scores);
   int32_t* idx = (int32_t*)(base + w.idx);
   int32_t* inv = (int32_t*)(base + w.inv);
-  void* Qc = base + w.Qc; void* Kc = base + w.Kc; void* Vt = base + w.Vt; void* Oc = base + w.Oc;
+  void* Vt = base + w.Vt; void* Oc = base + w.Oc;
   hipStream_t st = (hipStream_t)stream;
-  const int kvh = dm.group_mode ? dm.Hkv : dm.Hq;
   if ((rc = hip_status(tsa::launch_score(dm, Q, K, scores, base + w.score_ws, st), "tsa_forward(score)"))) return rc;
   if ((rc = hip_status(tsa::launch_select(dm, scores, k_keep, idx, inv, base + w.select_ws, st), "tsa_forward(select)"))) return rc;
-  if ((rc = hip_status(tsa::launch_compress_tiled(dm, Q, K, V, idx, k_keep, Qc, Kc, Vt, st), "tsa_forward(compress)"))) return rc;
-  if ((rc = hip_status(tsa::launch_attend(dm.B, dm.Hq, kvh, k_keep, dm.d, dm.scale, Qc, Kc, Vt, block_list,
-                                          max_blocks_per_row, Oc, nullptr, st), "tsa_forward(attend)"))) return rc;
-  if (O && (rc = hip_status(tsa::launch_decompress(dm, Oc, inv, k_keep, O, st), "tsa_forward(decompress)"))) return rc;
+  // Compression and decompression are folded into the attention kernel: it gathers Q and K rows
+  // through idx in its loads, writes the rows of O in its epilogue and clears the other rows; only
+  // V is gathered beforehand (into the transposed tiles the kernel's operands want).  The compacted
+  // output is materialised only for the residual update.
+  if ((rc = hip_status(tsa::launch_compress_tiled(dm, Q, K, V, idx, k_keep, nullptr, nullptr, Vt, st), "tsa_forward(V tiles)"))) return rc;
+  if ((rc = hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_keep, block_list, max_blocks_per_row,
+                                                residual ? Oc : nullptr, O, st), "tsa_forward(attend)"))) return rc;
   if (residual && (rc = hip_status(tsa::launch_residual(dm, Oc, idx, k_keep, residual, st), "tsa_forward(residual)"))) return rc;
   if (idx_out) {
     const size_t Hs = (size_t)dm.B * (dm.group_mode ? dm.Hkv : dm.Hq);

@@ -59,6 +59,16 @@ struct AttendArgs {
   int max_blocks;
   int BH, Hq, kvh, Lc, nq_tiles, nk_tiles;
   float c;                     // scale * log2(e)
+  // Fused form (gather in the loads, scatter in the epilogue): Q and K are the ORIGINAL tensors of
+  // L tokens (K with Hkv heads), compacted row r of selection row `sel` is token idx[sel][r];
+  // Vt holds the tiles of the gathered V.  Of (may be NULL) is the full-length output
+  // [B,Hq,L,d]: rows of selected tokens are written by the epilogue, all other rows are
+  // zero-filled by the workgroup that owns their token range (inv[sel][t] < 0).  O (the compacted
+  // output) may be NULL in this form.
+  const int32_t* idx;
+  const int32_t* inv;
+  __bf16* Of;
+  int L, Hkv;
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
@@ -243,7 +253,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const __bf16* base, 
 // every LDS fragment feeds two MFMAs.  QS = 1: 8 wavefronts of 32 rows, two per SIMD, which share
 // the SIMD's issue slots (a lone wavefront issues one vector instruction every ~8 clocks, two
 // together one every ~5) at the price of one LDS fragment per MFMA.
-template <int D, int QS>
+template <int D, int QS, bool FUSED>
 __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) {
   constexpr int kThreads = 512 / QS;
   constexpr int RW = 32 * QS;                     // query rows per wavefront
@@ -267,15 +277,23 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const int qt = a.nq_tiles - 1 - slot / heads_per_xcd;
   const int b = hp / a.Hq, hr = hp % a.Hq;
   const int g = a.Hq / a.kvh;
-  const int h = (hr % a.kvh) * g + hr / a.kvh;           // heads of one KV group are 8 apart in hp
+  const int n_grp = FUSED ? a.Hkv : a.kvh, g_grp = a.Hq / n_grp;
+  const int h = (hr % n_grp) * g_grp + hr / n_grp;       // heads of one KV group are 8 apart in hp
   const long long bh = (long long)b * a.Hq + h;
-  const long long bkv = (long long)b * a.kvh + h / g;
-  const long long head_bytes = (long long)a.Lc * ROWB;
+  const long long bkv = (long long)b * a.kvh + h / g;    // head of K^ / V^ (fused: of the index set and the V tiles)
+  // rows of Q and K: the compacted tensors, or (fused) the original ones addressed through idx
+  const int n_rows = FUSED ? a.L : a.Lc;
+  const long long head_bytes = (long long)n_rows * ROWB;
+  const long long k_head = FUSED ? (long long)b * a.Hkv + h / g_grp : bkv;
 
-  const __amdgpu_buffer_rsrc_t Qr = head_rsrc(a.Q + bh * a.Lc * D, head_bytes);
-  const __amdgpu_buffer_rsrc_t Kr = head_rsrc(a.K + bkv * a.Lc * D, head_bytes);
+  const __amdgpu_buffer_rsrc_t Qr = head_rsrc(a.Q + bh * n_rows * D, head_bytes);
+  const __amdgpu_buffer_rsrc_t Kr = head_rsrc(a.K + k_head * n_rows * D, head_bytes);
   const long long vt_bytes = (long long)a.nk_tiles * BN * ROWB;
   const __amdgpu_buffer_rsrc_t Vr = head_rsrc(a.Vt + bkv * (vt_bytes / 2), vt_bytes);
+  const int32_t* idx_row = FUSED ? a.idx + bkv * a.Lc : nullptr;
+  // index loads past the end of the set return 0 (token 0): such rows are only ever read as keys
+  // beyond every query of the workgroup, which causality masks
+  const __amdgpu_buffer_rsrc_t Ir = __builtin_amdgcn_make_buffer_rsrc((void*)idx_row, 0, FUSED ? a.Lc * 4 : 0, 0x00020000);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int q0 = qt * BM;
@@ -284,15 +302,35 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const float c = a.c;
   const float c_ = c;
 
+  // ---- fused form: zero rows of the full-length output.  The workgroup owns the tokens from its
+  // first selected token up to the next workgroup's first one (the first workgroup of a head starts
+  // at token 0, the last one ends at L) and clears those that are not selected.  Issued first: the
+  // stores drain while the tiles are computed.
+  if (FUSED && a.Of) {
+    constexpr int LPR = D / 8;
+    const int32_t* inv_row = a.inv + bkv * a.L;
+    const int tok_lo = qt == 0 ? 0 : idx_row[q0];
+    const int tok_hi = q0 + BM >= a.Lc ? a.L : idx_row[q0 + BM];
+    u32x4* orow = (u32x4*)(a.Of + bh * a.L * D) + (tid % LPR);
+    for (int t = tok_lo + tid / LPR; t < tok_hi; t += kThreads / LPR)
+      if (inv_row[t] < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, orow + (long long)t * LPR);
+  }
+
   // Q^T operand fragments (two 32-row sub-tiles) stay in registers for the whole kernel
   bf16x8 qf[QS][NS];
 #pragma unroll
-  for (int qs = 0; qs < QS; ++qs)
+  for (int qs = 0; qs < QS; ++qs) {
+    int qrow_off = (wrow0 + 32 * qs + lo) * ROWB;
+    if (FUSED) {
+      const int qr = wrow0 + 32 * qs + lo;
+      qrow_off = qr < a.Lc ? idx_row[qr] * ROWB : a.L * ROWB;   // past the end: out of the buffer's range, reads zeros
+    }
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(Qr, (wrow0 + 32 * qs + lo) * ROWB + 16 * hi + 32 * s, 0, 0);
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(Qr, qrow_off + 16 * hi + 32 * s, 0, 0);
       qf[qs][s] = __builtin_bit_cast(bf16x8, v);
     }
+  }
   // Wait for Q here, on every path: otherwise the compiler's wait-count bookkeeping carries these
   // loads as "possibly pending" into the main loop and makes every MFMA that reads a Q fragment
   // wait for the oldest in-flight K/V prefetch as well.
@@ -322,15 +360,24 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   // 8 * (piece % 8).. .  The tile's first key goes into the scalar offset of the buffer load.
   constexpr int kRowsPerPass = kThreads / (D / 8);
   const int st_row = tid / (D / 8), st_col = tid % (D / 8);
-  const int g_off = st_row * ROWB + 16 * st_col;                  // bytes, global side (K)
   const int lk_off = k_row_perm(st_row) * KS + 8 * st_col;        // elements, LDS side (K): permuted row order
   const int gv_off = 16 * tid;                                    // bytes, global side (V^T)
   const int lv_off = (tid >> 3) * VS + 8 * (tid & 7);             // elements, LDS side (V^T)
   constexpr int kVRowsPerPass = kThreads / 8;
-  auto load_k = [&](int k0, u32x4 (&reg)[CH]) {
+  // Rows of the next K tile to be loaded: ktok[i] = row of thread chunk i (fused: the token the
+  // compacted row stands for, fetched from idx one tile ahead of the K load that uses it).
+  int ktok[CH];
+  auto fetch_tok = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      if (FUSED) ktok[i] = __builtin_amdgcn_raw_buffer_load_b32(Ir, (st_row + i * kRowsPerPass) * 4, k0 * 4, 0);
+      else ktok[i] = k0 + st_row + i * kRowsPerPass;
+    }
+  };
+  auto load_k = [&](u32x4 (&reg)[CH]) {
 #pragma unroll
     for (int i = 0; i < CH; ++i)
-      reg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, g_off + i * kRowsPerPass * ROWB, k0 * ROWB, 0);
+      reg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, ktok[i] * ROWB + 16 * st_col, 0, 0);
   };
   auto load_v = [&](int k0, u32x4 (&reg)[CH]) {
 #pragma unroll
@@ -375,25 +422,31 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   };
 
   // ---- prologue
-  Tile T0 = gen.next(), T1 = gen.next(), T2 = gen.next();
+  Tile T0 = gen.next(), T1 = gen.next(), T2 = gen.next(), T3 = gen.next();
   u32x4 kreg[CH], vreg[CH];
   f32x16 sA[QS], sB[QS];
   uint32_t pA[QS][8], pB[QS][8];
   if (T0.k0 >= 0) {
-    load_k(T0.k0, kreg);
+    fetch_tok(T0.k0);
+    load_k(kreg);
     load_v(T0.k0, vreg);
     store_k(kc, kreg);
     store_v(vc, vreg);
     if (T1.k0 >= 0) {
-      load_k(T1.k0, kreg);
+      fetch_tok(T1.k0);
+      load_k(kreg);
       store_k(kn, kreg);
     }
   }
   __syncthreads();
   auto wave_active = [&](const Tile& t) -> bool { return t.k0 >= 0 && (t.use & half_bit) && t.k0 <= wrow0 + RW - 1; };
   if (T0.k0 >= 0) qk_half<D, QS>(kc, k_rd, qf, sA);
-  if (T2.k0 >= 0) load_k(T2.k0, kreg);
+  if (T2.k0 >= 0) {
+    fetch_tok(T2.k0);
+    load_k(kreg);
+  }
   if (T1.k0 >= 0) load_v(T1.k0, vreg);
+  if (T3.k0 >= 0) fetch_tok(T3.k0);
   if (wave_active(T0)) {
     if (T0.k0 + 31 > wrow0) mask_half<QS>(sA, T0.k0, hi, wrow0 + lo);
     softmax_max<ND, QS>(sA, c, m, l, o);
@@ -401,7 +454,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
 
   // Invariant at the top of an iteration: sA = S^T of the first half of tile T0, already masked
   // and already covered by the running max m (if this wavefront takes part in T0); K(T0) in kc,
-  // K(T1) in kn, V(T0) in vc; kreg = K(T2) and vreg = V(T1) are in flight.
+  // K(T1) in kn, V(T0) in vc; kreg = K(T2) and vreg = V(T1) are in flight; ktok = rows of T3.
   //
   // Order inside an iteration: every block of 16 MFMAs is issued next to vector work that does
   // not depend on it, so the matrix pipe and the VALU overlap within the wavefront:
@@ -446,7 +499,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     for (; t < n_fast; ++t) {
       float mxc[QS], mx[QS], ps0[QS], ps1[QS];
       f32x16 acc[QS];
-      const int kload = (t + 3) * BN * ROWB, vload = (t + 2) * BN * ROWB;
+      const int vload = (t + 2) * BN * ROWB, tokload = (t + 4) * BN;
 #pragma unroll
       for (int c = 0; c < kChunks; ++c) {
         const int blk = c / CPB, i = c % CPB, slot = c % kRing;
@@ -514,7 +567,9 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
           if (blk == 3 && TSA_PROBE < 4) {                 // K(t+2) -> kf, V(t+1) -> vn, then refill the registers
             if (i < CH) {
               *(u32x4*)(&kf[lk_off + i * kRowsPerPass * KS]) = kreg[i];
-              kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, g_off + i * kRowsPerPass * ROWB, kload, 0);
+              kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, ktok[i] * ROWB + 16 * st_col, 0, 0);
+              if (FUSED) ktok[i] = __builtin_amdgcn_raw_buffer_load_b32(Ir, (st_row + i * kRowsPerPass) * 4, tokload * 4, 0);
+              else ktok[i] = tokload + st_row + i * kRowsPerPass;
             } else if (i < 2 * CH) {
               *(u32x4*)(&vn[lv_off + (i - CH) * kVRowsPerPass * VS]) = vreg[i - CH];
               vreg[i - CH] = __builtin_amdgcn_raw_buffer_load_b128(Vr, gv_off + (i - CH) * kThreads * 16, vload, 0);
@@ -536,8 +591,8 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     }
     if (t > 0) {                                           // hand over to the general loop
       auto tile_at = [&](int i) { return i < gen.plain_n ? Tile{i * BN, 3} : Tile{-1, 0}; };
-      T0 = tile_at(t); T1 = tile_at(t + 1); T2 = tile_at(t + 2);
-      gen.plain_i = t + 3;
+      T0 = tile_at(t); T1 = tile_at(t + 1); T2 = tile_at(t + 2); T3 = tile_at(t + 3);
+      gen.plain_i = t + 4;
     }
   }
 
@@ -559,11 +614,12 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     }
     if (T2.k0 >= 0) store_k(kf, kreg);
     if (T1.k0 >= 0) store_v(vn, vreg);
-    const Tile T3 = gen.next();
-    if (T3.k0 >= 0) load_k(T3.k0, kreg);
+    if (T3.k0 >= 0) load_k(kreg);
     if (T2.k0 >= 0) load_v(T2.k0, vreg);
+    const Tile T4 = gen.next();
+    if (T4.k0 >= 0) fetch_tok(T4.k0);
     lds_barrier();
-    T0 = T1; T1 = T2; T2 = T3;
+    T0 = T1; T1 = T2; T2 = T3; T3 = T4;
     rotate();
   }
 
@@ -574,7 +630,9 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     const float lt = l[qs] + __shfl_xor(l[qs], 32);
     const float inv_l = lt > 0.f ? 1.0f / lt : 0.f;
     if (qrow < a.Lc) {
-      __bf16* orow = a.O + (bh * a.Lc + qrow) * D;
+      __bf16* orow = a.O ? a.O + (bh * a.Lc + qrow) * D : nullptr;
+      __bf16* frow = nullptr;                       // fused: the token's row of the full-length output
+      if (FUSED && a.Of) frow = a.Of + (bh * a.L + idx_row[qrow]) * D;
 #pragma unroll
       for (int dt = 0; dt < ND; ++dt)
 #pragma unroll
@@ -582,11 +640,26 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
           u32x2 w;
           w[0] = pack_bf16(o[qs][dt][4 * q4 + 0] * inv_l, o[qs][dt][4 * q4 + 1] * inv_l);
           w[1] = pack_bf16(o[qs][dt][4 * q4 + 2] * inv_l, o[qs][dt][4 * q4 + 3] * inv_l);
-          *(u32x2*)(orow + 32 * dt + 8 * q4 + 4 * hi) = w;
+          if (orow) *(u32x2*)(orow + 32 * dt + 8 * q4 + 4 * hi) = w;
+          if (FUSED && frow) *(u32x2*)(frow + 32 * dt + 8 * q4 + 4 * hi) = w;
         }
       if (a.lse && hi == 0) a.lse[bh * a.Lc + qrow] = (m[qs] + log2f(lt)) * kLn2;
     }
   }
+}
+
+}  // namespace
+
+namespace {
+
+template <bool FUSED>
+hipError_t launch_any(AttendArgs& a, int d, hipStream_t st) {
+  a.nq_tiles = (a.Lc + BM - 1) / BM;
+  a.nk_tiles = (a.Lc + BN - 1) / BN;
+  const unsigned grid = 8u * (unsigned)((a.BH + 7) / 8) * (unsigned)a.nq_tiles;
+  if (d == 128) attend_kernel<128, kQS, FUSED><<<grid, 512 / kQS, 0, st>>>(a);
+  else attend_kernel<64, kQS, FUSED><<<grid, 512 / kQS, 0, st>>>(a);
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -598,13 +671,21 @@ hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale
   a.Q = (const __bf16*)Qc; a.K = (const __bf16*)Kc; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
   a.lse = lse; a.block_list = block_list; a.max_blocks = max_blocks_per_row;
   a.BH = B * Hq; a.Hq = Hq; a.kvh = kv_heads; a.Lc = Lc;
-  a.nq_tiles = (Lc + BM - 1) / BM;
-  a.nk_tiles = (Lc + BN - 1) / BN;
   a.c = scale * kLog2e;
-  const unsigned grid = 8u * (unsigned)((a.BH + 7) / 8) * (unsigned)a.nq_tiles;
-  if (d == 128) attend_kernel<128, kQS><<<grid, 512 / kQS, 0, st>>>(a);
-  else attend_kernel<64, kQS><<<grid, 512 / kQS, 0, st>>>(a);
-  return hipGetLastError();
+  a.idx = nullptr; a.inv = nullptr; a.Of = nullptr; a.L = Lc; a.Hkv = kv_heads;
+  return launch_any<false>(a, d, st);
+}
+
+hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, const void* Vt, const int32_t* idx,
+                               const int32_t* inv, int k_keep, const int32_t* block_list, int max_blocks_per_row,
+                               void* Oc, void* O, hipStream_t st) {
+  AttendArgs a;
+  a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
+  a.lse = nullptr; a.block_list = block_list; a.max_blocks = max_blocks_per_row;
+  a.BH = dm.B * dm.Hq; a.Hq = dm.Hq; a.kvh = dm.group_mode ? dm.Hkv : dm.Hq; a.Lc = k_keep;
+  a.c = dm.scale * kLog2e;
+  a.idx = idx; a.inv = inv; a.Of = (__bf16*)O; a.L = dm.L; a.Hkv = dm.Hkv;
+  return launch_any<true>(a, dm.d, st);
 }
 
 }  // namespace tsa

@@ -162,7 +162,8 @@ __global__ __launch_bounds__(kThreads) void v_tile_kernel(const u32x4* __restric
 // Stage 1 compression for the fused layer: one workgroup = kKeyTile consecutive compacted rows of one
 // query head: Q and K rows are copied as in compress_kernel, V rows go through LDS into the
 // tile of V^T the attention kernel will read.  With per-group sets only the first query head
-// of a group moves K and V.
+// of a group moves K and V.  With Qc == NULL only the V tiles are built (the attention kernel then
+// gathers Q and K rows itself).
 struct CompressTiledArgs {
   const u32x4* Q; const u32x4* K; const u32x4* V; const int32_t* idx;
   u32x4* Qc; u32x4* Kc; __bf16* Vt;
@@ -182,6 +183,7 @@ __global__ __launch_bounds__(kThreads) void compress_tiled_kernel(CompressTiledA
   const long long bkv = b * a.Hkv + h / g;
   const long long sel_head = a.group_mode ? bkv : bh;
   const bool kv_owner = a.group_mode == 0 || h % g == 0;
+  if (!a.Qc && !kv_owner) return;            // nothing to do; the same for every thread of the workgroup
   const int r0 = t * kKeyTile;
   if (threadIdx.x < kKeyTile) tok[threadIdx.x] = r0 + (int)threadIdx.x < a.k ? a.idx[sel_head * a.k + r0 + threadIdx.x] : -1;
   __syncthreads();
@@ -191,9 +193,9 @@ __global__ __launch_bounds__(kThreads) void compress_tiled_kernel(CompressTiledA
     const int tk = tok[r];
     u32x4 v = {0u, 0u, 0u, 0u};
     if (tk >= 0) {
-      a.Qc[(bh * a.k + r0 + r) * LPR + col] = a.Q[(bh * a.L + tk) * LPR + col];
+      if (a.Qc) a.Qc[(bh * a.k + r0 + r) * LPR + col] = a.Q[(bh * a.L + tk) * LPR + col];
       if (kv_owner) {
-        a.Kc[(sel_head * a.k + r0 + r) * LPR + col] = a.K[(bkv * a.L + tk) * LPR + col];
+        if (a.Qc) a.Kc[(sel_head * a.k + r0 + r) * LPR + col] = a.K[(bkv * a.L + tk) * LPR + col];
         v = a.V[(bkv * a.L + tk) * LPR + col];
       }
     }
