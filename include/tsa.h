@@ -144,6 +144,24 @@ int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void*
 int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, const int32_t* inv,
                    int32_t k_keep, void* O, void* residual, void* stream);
 
+/* Stage 1 + attention + Stage 2 in two launches, the form tsa_forward uses.  Same results as
+ * tsa_compress -> tsa_attend -> tsa_decompress, but the compacted Q, K and O never exist in memory.
+ *
+ * tsa_compress_v_tiles: gathers the rows S_h of V into 64-key transposed tiles,
+ *   Vt [B,Hs',ceil(k_keep/64),d,64] bf16 (Hs' = Hq, or Hkv with group_mode 1; keys past k_keep zero),
+ *   vt_bytes >= tsa_attend_workspace_bytes(desc, k_keep, Hs'), Vt 256-byte aligned.
+ * tsa_attend_fused: causal attention over the compacted set, reading row r of head h as
+ *   Q[b,h,idx[r],:], K[b,h/g,idx[r],:] (original tensors) and the V tiles; writes
+ *   O [B,Hq,L,d] (may be NULL): O[b,h,idx[r],:] = output row r, every other row zero (needs inv), and/or
+ *   Oc [B,Hq,k_keep,d] (may be NULL): the compacted output, as tsa_attend would.
+ *   block_list as in tsa_attend. */
+int tsa_compress_v_tiles(const tsa_desc* desc, const void* V, const int32_t* idx, int32_t k_keep,
+                         void* Vt, size_t vt_bytes, void* stream);
+int tsa_attend_fused(const tsa_desc* desc, const void* Q, const void* K, const void* Vt,
+                     const int32_t* idx, const int32_t* inv, int32_t k_keep,
+                     const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
+                     void* O, void* Oc, void* stream);
+
 /* The whole layer on one stream, no host synchronisation:
  * score -> select -> compress -> attend -> decompress (Figure 3 of the paper).  Same results as the
  * five calls in a row; inside, the gather of Q and K rows happens in the attention kernel's loads

@@ -15,7 +15,7 @@ from . import build as _build
 TSA_OK, TSA_ERR_ARG, TSA_ERR_UNSUPPORTED, TSA_ERR_WORKSPACE, TSA_ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_bytes", "tsa_score", "tsa_coverage_budget",
-           "tsa_select", "tsa_compress", "tsa_attend_workspace_bytes", "tsa_attend", "tsa_decompress", "tsa_forward",
+           "tsa_select", "tsa_compress", "tsa_attend_workspace_bytes", "tsa_attend", "tsa_decompress", "tsa_compress_v_tiles", "tsa_attend_fused", "tsa_forward",
            "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe")
 
 
@@ -70,6 +70,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_compress.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.tsa_attend.restype = ctypes.c_int
     lib.tsa_attend.argtypes = [dp, vp, vp, vp, i32, i32, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.tsa_compress_v_tiles.restype = ctypes.c_int
+    lib.tsa_compress_v_tiles.argtypes = [dp, vp, vp, i32, vp, sz, vp]
+    lib.tsa_attend_fused.restype = ctypes.c_int
+    lib.tsa_attend_fused.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp]
     lib.tsa_mfma_probe.restype = ctypes.c_int
     lib.tsa_mfma_probe.argtypes = [vp, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32), vp]
     lib.tsa_attend_workspace_bytes.restype = sz
@@ -163,6 +167,16 @@ def tsa_attend(desc, Qc, Kc, Vc, Lc, kv_heads, Oc, ws, lse=None, block_list=None
 def tsa_decompress(desc, Oc, idx, inv, k_keep, O=None, residual=None):
     _check(load_library().tsa_decompress(ctypes.byref(desc), _ptr(Oc), _ptr(idx), _ptr(inv), k_keep,
                                          _ptr(O), _ptr(residual), _stream()))
+
+
+def tsa_compress_v_tiles(desc, V, idx, k_keep, Vt):
+    p, n = _ws(Vt)
+    _check(load_library().tsa_compress_v_tiles(ctypes.byref(desc), _ptr(V), _ptr(idx), k_keep, p, n, _stream()))
+
+
+def tsa_attend_fused(desc, Q, K, Vt, idx, inv, k_keep, O=None, Oc=None, block_list=None, block_size=0, max_blocks_per_row=0):
+    _check(load_library().tsa_attend_fused(ctypes.byref(desc), _ptr(Q), _ptr(K), _ptr(Vt), _ptr(idx), _ptr(inv), k_keep,
+                                           _ptr(block_list), block_size, max_blocks_per_row, _ptr(O), _ptr(Oc), _stream()))
 
 
 def tsa_forward(desc, Q, K, V, k_keep, O, ws, residual=None, idx_out=None,

@@ -212,6 +212,33 @@ int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, con
   return TSA_OK;
 }
 
+int tsa_compress_v_tiles(const tsa_desc* desc, const void* V, const int32_t* idx, int32_t k_keep,
+                         void* Vt, size_t vt_bytes, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep))) return rc;
+  if ((rc = check_ptr(V, "V")) || (rc = check_ptr(idx, "idx"))) return rc;
+  if ((rc = check_ws(Vt, vt_bytes, tsa::v_tiles_bytes(dm.B, dm.group_mode ? dm.Hkv : dm.Hq, k_keep, dm.d)))) return rc;
+  return hip_status(tsa::launch_compress_tiled(dm, nullptr, nullptr, V, idx, k_keep, nullptr, nullptr, Vt, (hipStream_t)stream),
+                    "tsa_compress_v_tiles");
+}
+
+int tsa_attend_fused(const tsa_desc* desc, const void* Q, const void* K, const void* Vt,
+                     const int32_t* idx, const int32_t* inv, int32_t k_keep,
+                     const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
+                     void* O, void* Oc, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep))) return rc;
+  if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(Vt, "Vt")) || (rc = check_ptr(idx, "idx"))) return rc;
+  if (!O && !Oc) return fail(TSA_ERR_ARG, "both O and Oc are NULL");
+  if ((rc = check_ptr(O, "O", true)) || (rc = check_ptr(Oc, "Oc", true))) return rc;
+  if (O && (rc = check_ptr(inv, "inv"))) return rc;
+  if ((rc = check_block_list(block_list, block_size, max_blocks_per_row))) return rc;
+  return hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_keep, block_list, max_blocks_per_row, Oc, O,
+                                             (hipStream_t)stream), "tsa_attend_fused");
+}
+
 int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* V, int32_t k_keep,
                 const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
                 void* O, void* residual, int32_t* idx_out,

@@ -263,3 +263,53 @@ def test_forward_small(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant):
     gu.assert_output_close(gu.from_dev(O), ref["O"], "forward")
     sel = ref["inv"] >= 0
     assert not gu.from_dev(O)[np.repeat(~sel, Hq // Hs, axis=1)].any()
+
+
+@pytest.mark.parametrize("Hq,Hkv,L,d,k,group_mode,with_blocks", [
+    (4, 2, 1500, 128, 700, 0, False),
+    (6, 2, 1203, 128, 333, 1, False),
+    (4, 4, 900, 64, 900, 0, False),
+    (4, 2, 2100, 128, 1100, 0, True),
+])
+def test_fused_path_equals_the_separate_calls(tsa, Hq, Hkv, L, d, k, group_mode, with_blocks):
+    """tsa_forward / tsa_compress_v_tiles + tsa_attend_fused against tsa_score -> tsa_select ->
+    tsa_compress -> tsa_attend -> tsa_decompress on the same inputs: gather and scatter are copies
+    and the arithmetic is the same, so every output must match bit for bit (the separate calls are
+    the ones checked against the oracle above)."""
+    r = _rng(900 + L)
+    Lq = 64
+    Q, K, V = (gu.to_dev(gu.rand_bits(r, (1, h, L, d))) for h in (Hq, Hkv, Hkv))
+    desc = tsa.make_desc(1, Hq, Hkv, L, d, Lq, group_mode=group_mode)
+    Hs = Hkv if group_mode else Hq
+    ws = _ws(tsa, desc, k)
+    bl = bl_kw = None
+    kw = {}
+    if with_blocks:
+        bl = torch.from_numpy(orc.lambda_block_list(k, 128, 256, 1)).to(gu.DEV)
+        kw = dict(block_list=bl, block_size=128, max_blocks_per_row=bl.shape[1])
+    # separate calls
+    s = torch.empty((1, Hq, L), dtype=torch.float32, device=gu.DEV)
+    idx = torch.empty((1, Hs, k), dtype=torch.int32, device=gu.DEV)
+    inv = torch.empty((1, Hs, L), dtype=torch.int32, device=gu.DEV)
+    Qc = torch.empty((1, Hq, k, d), dtype=torch.bfloat16, device=gu.DEV)
+    Kc = torch.empty((1, Hs, k, d), dtype=torch.bfloat16, device=gu.DEV)
+    Vc, Oc, O1 = torch.empty_like(Kc), torch.empty_like(Qc), torch.full((1, Hq, L, d), 5.0, dtype=torch.bfloat16, device=gu.DEV)
+    tsa.tsa_score(desc, Q, K, s, ws)
+    tsa.tsa_select(desc, s, k, idx, inv, ws)
+    tsa.tsa_compress(desc, Q, K, V, idx, k, Qc, Kc, Vc)
+    tsa.tsa_attend(desc, Qc, Kc, Vc, k, Hs, Oc, tsa.alloc_attend_workspace(desc, k, Hs, gu.DEV), **kw)
+    tsa.tsa_decompress(desc, Oc, idx, inv, k, O=O1)
+    # the two fused launches on the same index sets
+    Vt = tsa.alloc_attend_workspace(desc, k, Hs, gu.DEV)
+    O2 = torch.full_like(O1, 7.0)
+    Oc2 = torch.full_like(Oc, 7.0)
+    tsa.tsa_compress_v_tiles(desc, V, idx, k, Vt)
+    tsa.tsa_attend_fused(desc, Q, K, Vt, idx, inv, k, O=O2, Oc=Oc2, **kw)
+    # the whole layer
+    O3 = torch.full_like(O1, 9.0)
+    idx3 = torch.empty_like(idx)
+    tsa.tsa_forward(desc, Q, K, V, k, O3, ws, idx_out=idx3, **kw)
+    torch.cuda.synchronize()
+    assert torch.equal(idx3, idx)
+    assert torch.equal(Oc2, Oc)
+    assert torch.equal(O2, O1) and torch.equal(O3, O1)
