@@ -53,6 +53,9 @@ typedef struct tsa_desc {
   int32_t force_first;  /* tokens t < force_first are always kept (score treated as +inf); default 0 */
   int32_t force_last;   /* tokens t >= L - force_last are always kept; default 0 */
   float   scale;        /* softmax scale; 0 means 1/sqrt(d) */
+  int32_t block_list_per_head; /* 0: one block list shared by all heads; 1: one list per (b, h),
+                                  block_list is [B,Hq,ceil(Lc/block_size),max_blocks_per_row] (block-sparse
+                                  methods pick a different pattern for every head) */
 } tsa_desc;
 
 /* Version of this ABI (increases when a signature changes). */
@@ -117,7 +120,8 @@ int tsa_compress(const tsa_desc* desc, const void* Q, const void* K, const void*
  *   Qc [B,Hq,Lc,d] bf16;  Kc, Vc [B,kv_heads,Lc,d] bf16 with Hq % kv_heads == 0
  *   Oc [B,Hq,Lc,d] bf16 out;  lse [B,Hq,Lc] fp32 out or NULL (natural-log sum-exp of the scaled logits)
  *   block_list: NULL for plain causal attention.  Otherwise [ceil(Lc/block_size), max_blocks_per_row]
- *   int32 on the device, shared by all heads: row qb lists, in ascending order and padded with -1,
+ *   int32 on the device, shared by all heads (or one such table per (b, h), see
+ *   tsa_desc.block_list_per_head): row qb lists, in ascending order and padded with -1,
  *   the key blocks that query block qb may see (composition with a block-sparse pattern in
  *   compacted index space, Section 1 / Appendix "other sparse attention methods").  Entries > qb
  *   are ignored; the diagonal block is causal inside.  block_size must be 128.

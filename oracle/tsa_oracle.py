@@ -260,6 +260,8 @@ def attend(Qc, Kc, Vc, scale: float | None = None, block_list=None, block_size: 
     Qc [B,Hq,Lc,d]; Kc,Vc [B,Hk,Lc,d] with Hq % Hk == 0 (head h reads h // (Hq/Hk)).
     Row r attends to columns c <= r; with a block list, additionally only to
     columns whose block c // block_size is listed for block r // block_size.
+    block_list is [nQb, width] (one pattern for all heads) or [B, Hq, nQb, width]
+    (one per head), rows padded with -1.
     `rows`: optional 1-D array of row numbers; then only those rows are computed
     and the result has shape [B,Hq,len(rows),d].  Returns float64 (not rounded)."""
     Qc = np.asarray(Qc, dtype=np.float64)
@@ -272,20 +274,24 @@ def attend(Qc, Kc, Vc, scale: float | None = None, block_list=None, block_size: 
         scale = 1.0 / math.sqrt(d)
     rsel = np.arange(Lc) if rows is None else np.asarray(rows, dtype=np.int64)
     cols = np.arange(Lc)
-    allowed = cols[None, :] <= rsel[:, None]
-    if block_list is not None:
-        bl = np.asarray(block_list)
+    causal = cols[None, :] <= rsel[:, None]
+
+    def block_mask(table):
         nb = (Lc + block_size - 1) // block_size
-        blk_ok = np.zeros((bl.shape[0], nb), dtype=bool)
-        for qb in range(bl.shape[0]):
-            for kb in bl[qb]:
+        blk_ok = np.zeros((table.shape[0], nb), dtype=bool)
+        for qb in range(table.shape[0]):
+            for kb in table[qb]:
                 if kb >= 0:
                     blk_ok[qb, kb] = True
-        allowed &= blk_ok[rsel // block_size][:, cols // block_size]
+        return blk_ok[rsel // block_size][:, cols // block_size]
+
+    bl = None if block_list is None else np.asarray(block_list)
+    shared = causal if bl is None else (causal & block_mask(bl) if bl.ndim == 2 else None)
     out = np.zeros((B, Hq, len(rsel), d), dtype=np.float64)
     lse = np.zeros((B, Hq, len(rsel)), dtype=np.float64)
     for b in range(B):
         for h in range(Hq):
+            allowed = shared if shared is not None else causal & block_mask(bl[b, h])
             y = scale * (Qc[b, h, rsel] @ Kc[b, h // g].T)
             y = np.where(allowed, y, -np.inf)
             m = y.max(axis=1, keepdims=True)

@@ -56,6 +56,7 @@ struct AttendArgs {
   __bf16* O;
   float* lse;
   const int32_t* block_list;
+  long long bl_head_stride;    // elements between the block lists of consecutive (b, h); 0 = one shared list
   int max_blocks;
   int BH, Hq, kvh, Lc, nq_tiles, nk_tiles;
   float c;                     // scale * log2(e)
@@ -345,10 +346,11 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   if (!gen.plain) {
     const int nqb = (a.Lc + kBlock - 1) / kBlock;
     const int qa = 2 * qt, qb = 2 * qt + 1;
-    gen.la = a.block_list + (long long)qa * a.max_blocks;
+    const int32_t* bl = a.block_list + bh * a.bl_head_stride;
+    gen.la = bl + (long long)qa * a.max_blocks;
     gen.ca = count_valid(gen.la, a.max_blocks, qa);
     if (qb < nqb) {
-      gen.lb = a.block_list + (long long)qb * a.max_blocks;
+      gen.lb = bl + (long long)qb * a.max_blocks;
       gen.cb = count_valid(gen.lb, a.max_blocks, qb);
     }
   }
@@ -665,9 +667,10 @@ hipError_t launch_any(AttendArgs& a, int d, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
-                         const void* Vt, const int32_t* block_list, int max_blocks_per_row, void* Oc, float* lse,
-                         hipStream_t st) {
+                         const void* Vt, const int32_t* block_list, int max_blocks_per_row, int block_list_per_head,
+                         void* Oc, float* lse, hipStream_t st) {
   AttendArgs a;
+  a.bl_head_stride = block_list_per_head ? (long long)((Lc + kBlock - 1) / kBlock) * max_blocks_per_row : 0;
   a.Q = (const __bf16*)Qc; a.K = (const __bf16*)Kc; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
   a.lse = lse; a.block_list = block_list; a.max_blocks = max_blocks_per_row;
   a.BH = B * Hq; a.Hq = Hq; a.kvh = kv_heads; a.Lc = Lc;
@@ -682,6 +685,7 @@ hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, con
   AttendArgs a;
   a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
   a.lse = nullptr; a.block_list = block_list; a.max_blocks = max_blocks_per_row;
+  a.bl_head_stride = dm.block_list_per_head ? (long long)((k_keep + kBlock - 1) / kBlock) * max_blocks_per_row : 0;
   a.BH = dm.B * dm.Hq; a.Hq = dm.Hq; a.kvh = dm.group_mode ? dm.Hkv : dm.Hq; a.Lc = k_keep;
   a.c = dm.scale * kLog2e;
   a.idx = idx; a.inv = inv; a.Of = (__bf16*)O; a.L = dm.L; a.Hkv = dm.Hkv;

@@ -215,3 +215,29 @@ def make_residual(cfg: dict, seed: int) -> np.ndarray:
     rng = np.random.Generator(np.random.PCG64([seed, 104729]))
     x = rng.standard_normal((cfg["B"], cfg["L"], cfg["Hq"] * cfg["d"]), dtype=np.float32)
     return f32_to_bf16_bits(x)
+
+
+def vertical_slash_block_lists(B: int, Hq: int, n_blocks: int, seed: int, n_vertical: int = 3, slash_blocks: int = 2,
+                               n_extra: int = 2) -> np.ndarray:
+    """Per-head block lists of the "vertical + slash" kind block-sparse prefill methods produce, in
+    compacted index space: for head (b, h) query block qb may see (a) the first key block, (b) the
+    head's own n_vertical seeded "vertical" key blocks (columns every later query sees), (c) the
+    slash: the diagonal block and the slash_blocks blocks before it, (d) n_extra seeded blocks of its
+    own below the diagonal.  Returns [B, Hq, n_blocks, width] int32, every row ascending, without
+    duplicates, entries <= qb, padded with -1.  A stand-in for the patterns of the block-sparse
+    methods the paper composes with (their pattern search is not part of this library)."""
+    rng = np.random.Generator(np.random.PCG64([seed, 77]))
+    width = 1 + n_vertical + slash_blocks + 1 + n_extra
+    out = np.full((B, Hq, n_blocks, width), -1, dtype=np.int32)
+    for b in range(B):
+        for h in range(Hq):
+            vertical = rng.integers(0, n_blocks, size=n_vertical)
+            for qb in range(n_blocks):
+                s = {0, qb}
+                s.update(int(v) for v in vertical if v <= qb)
+                s.update(range(max(0, qb - slash_blocks), qb + 1))
+                if qb > 0:
+                    s.update(int(v) for v in rng.integers(0, qb, size=n_extra))
+                row = sorted(s)
+                out[b, h, qb, :len(row)] = row
+    return out

@@ -313,3 +313,41 @@ def test_fused_path_equals_the_separate_calls(tsa, Hq, Hkv, L, d, k, group_mode,
     assert torch.equal(idx3, idx)
     assert torch.equal(Oc2, Oc)
     assert torch.equal(O2, O1) and torch.equal(O3, O1)
+
+
+@pytest.mark.parametrize("Hq,Hk,Lc,d", [(4, 2, 1000, 128), (3, 3, 1500, 64)])
+def test_attend_per_head_block_lists(tsa, Hq, Hk, Lc, d):
+    """Block-sparse composition with a different pattern for every head (vertical + slash)."""
+    from paper_2602_03216_amd import inputs as gen
+    r = _rng(1500 + Lc)
+    B, Bs = 2, 128
+    Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d))
+    bl = gen.vertical_slash_block_lists(B, Hq, (Lc + Bs - 1) // Bs, seed=Lc)
+    desc = tsa.make_desc(B, Hq, Hk, Lc, d, 1, block_list_per_head=1)
+    O = torch.empty((B, Hq, Lc, d), dtype=torch.bfloat16, device=gu.DEV)
+    tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, Hk, O, tsa.alloc_attend_workspace(desc, Lc, Hk, gu.DEV),
+                   block_list=torch.from_numpy(bl).to(gu.DEV), block_size=Bs, max_blocks_per_row=bl.shape[-1])
+    want = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), block_list=bl, block_size=Bs)
+    gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(per-head block lists)")
+
+
+def test_forward_with_per_head_block_lists(tsa):
+    """Token selection first, then a per-head block-sparse pattern in compacted space: the whole layer
+    against the oracle's."""
+    from paper_2602_03216_amd import inputs as gen
+    from tests.margin import enforce_margin
+    Hq, Hkv, L, d, Lq, k, Bs = 4, 2, 2000, 128, 64, 900, 128
+    cfg = dict(id=91, name="small", B=1, Hq=Hq, Hkv=Hkv, L=L, d=d, last_q=Lq, plant="direction", n_plant=20, norm_factor=3.0,
+               frac_plant=0.1, boost=4.0, sink_boost=6.0, n_sink=4, zipf_a=1.2)
+    inp = gen.make_inputs(cfg, seed=1234)
+    enforce_margin(inp, [k], 0)
+    bl = gen.vertical_slash_block_lists(1, Hq, (k + Bs - 1) // Bs, seed=9)
+    desc = tsa.make_desc(1, Hq, Hkv, L, d, Lq, block_list_per_head=1)
+    O = torch.full((1, Hq, L, d), 3.0, dtype=torch.bfloat16, device=gu.DEV)
+    idx = torch.zeros((1, Hq, k), dtype=torch.int32, device=gu.DEV)
+    tsa.tsa_forward(desc, gu.to_dev(inp.Q), gu.to_dev(inp.K), gu.to_dev(inp.V), k, O, _ws(tsa, desc, k), idx_out=idx,
+                    block_list=torch.from_numpy(bl).to(gu.DEV), block_size=Bs, max_blocks_per_row=bl.shape[-1])
+    torch.cuda.synchronize()
+    ref = orc.forward(inp.Q, inp.K, inp.V, k, Lq, block_list=bl, block_size=Bs)
+    assert np.array_equal(idx.cpu().numpy(), ref["idx"])
+    gu.assert_output_close(gu.from_dev(O), ref["O"], "forward(per-head block lists)")

@@ -464,6 +464,36 @@ def test_lambda_block_list_against_pair_predicate():
     assert np.allclose(orc.attend(Q, K, V, block_list=bl_all, block_size=Bs), orc.attend(Q, K, V), atol=1e-15)
 
 
+def test_attend_per_head_block_lists_against_pair_predicate():
+    """Per-head block lists (vertical + slash patterns): the oracle against a pure-Python loop that
+    applies 'pair (r, c) is visible iff c <= r and block(c) is listed for block(r) of THIS head'."""
+    from paper_2602_03216_amd import inputs as gen
+    r = _rng(77)
+    B, Hq, Hk, Lc, d, Bs = 1, 3, 1, 70, 4, 16
+    nb = (Lc + Bs - 1) // Bs
+    bl = gen.vertical_slash_block_lists(B, Hq, nb, seed=5, n_vertical=1, slash_blocks=0, n_extra=1)
+    assert bl.shape[:3] == (B, Hq, nb) and any(not np.array_equal(bl[0, 0], bl[0, h]) for h in range(1, Hq))
+    for h in range(Hq):
+        for qb in range(nb):
+            row = [int(v) for v in bl[0, h, qb] if v >= 0]
+            assert row == sorted(set(row)) and row[0] == 0 and row[-1] == qb     # ascending, sink and diagonal present
+    Q, K, V = r.standard_normal((B, Hq, Lc, d)), r.standard_normal((B, Hk, Lc, d)), r.standard_normal((B, Hk, Lc, d))
+    got = orc.attend(Q, K, V, block_list=bl, block_size=Bs)
+    for h in range(Hq):
+        for row in range(Lc):
+            listed = set(int(v) for v in bl[0, h, row // Bs] if v >= 0)
+            vis = [c for c in range(row + 1) if c // Bs in listed]
+            w = [math.exp(sum(Q[0, h, row, j] * K[0, 0, c, j] for j in range(d)) / math.sqrt(d)) for c in vis]
+            z = sum(w)
+            for j in range(d):
+                want = sum(wi * V[0, 0, c, j] for wi, c in zip(w, vis)) / z
+                assert abs(got[0, h, row, j] - want) < 1e-12
+    # a shared list given per head is the same thing
+    lam = orc.lambda_block_list(Lc, Bs, 16, 1)
+    per_head = np.broadcast_to(lam, (B, Hq) + lam.shape).copy()
+    assert np.array_equal(orc.attend(Q, K, V, block_list=lam, block_size=Bs), orc.attend(Q, K, V, block_list=per_head, block_size=Bs))
+
+
 # ----------------------------------------------------------------------------- layer selection
 
 def test_layer_drift_closed_forms_and_brute_force():
