@@ -85,6 +85,29 @@ size_t tsa_workspace_bytes(const tsa_desc* desc, int32_t k_keep);
 int tsa_score(const tsa_desc* desc, const void* Q, const void* K, float* scores,
               void* ws, size_t ws_bytes, void* stream);
 
+/* Scoring from other query sets -- the paper's scoring ablation (appendix, "Token Scoring Methods":
+ * randomly selected queries, or a pooled query tensor, in place of the most recent queries).
+ *
+ * tsa_score_queries: as tsa_score, but the scoring queries are the rows of Qsel [B,Hq,n,d] bf16 (device),
+ *   query j sitting at position qpos[j]: s[b,h,t] = sum_j softmax_t(scale Qsel[b,h,j].k_t) over keys
+ *   t <= qpos[j].  qpos: HOST array of n ints in [0, L), ascending (it travels in the kernel
+ *   arguments); n must equal desc->last_q (which sizes the workspace).  tsa_score is the case
+ *   Qsel = Q[:, :, L-n:], qpos = L-n .. L-1.
+ * tsa_gather_queries: Qsel[b,h,j,:] = Q[b,h,qpos[j],:] -- the rows of randomly selected queries; the
+ *   caller draws the positions (seeded, sorted) and passes them in, 1 <= n <= 128.
+ * tsa_pool_queries: query-only pooling: the L rows of every head are cut into n_pool contiguous
+ *   segments (rows floor(j L / n_pool) .. ceil((j+1) L / n_pool) - 1) and averaged (fp32 sums in a
+ *   fixed order, one rounding to bf16): Qsel [B,Hq,n_pool,d] out; qpos (HOST, out, may be NULL)
+ *   receives the last row of each segment, the position a pooled query scores from.  The paper
+ *   does not give the pooling window or the causal treatment: n_pool = 1 is a single mean query
+ *   that sees every key. */
+int tsa_score_queries(const tsa_desc* desc, const void* Qsel, const int32_t* qpos, int32_t n, const void* K,
+                      float* scores, void* ws, size_t ws_bytes, void* stream);
+int tsa_gather_queries(const tsa_desc* desc, const void* Q, const int32_t* qpos, int32_t n, void* Qsel, void* stream);
+size_t tsa_pool_queries_workspace_bytes(const tsa_desc* desc, int32_t n_pool);
+int tsa_pool_queries(const tsa_desc* desc, const void* Q, int32_t n_pool, void* Qsel, int32_t* qpos,
+                     void* ws, size_t ws_bytes, void* stream);
+
 /* Dynamic Token Coverage budget -- Algorithm 1, steps "aggregate and normalize token scores across
  * heads", "sort tokens by ascending importance" and "determine the number of sparse token":
  * s_l[t] = sum_h scores[b,h,t] (fp32, head order), normalised by its total over t; k_sparse is the

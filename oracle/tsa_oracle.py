@@ -110,6 +110,50 @@ def score(Q: np.ndarray, K: np.ndarray, last_q: int, scale: float | None = None)
     return s
 
 
+def score_queries(Qsel: np.ndarray, qpos, K: np.ndarray, scale: float | None = None) -> np.ndarray:
+    """Token scores from an arbitrary set of scoring queries (the scoring ablation of the paper's
+    appendix: randomly sampled queries, or a pooled query, in place of the most recent ones):
+    s[b,h,t] = sum_j softmax_t(scale Qsel[b,h,j].k_t), query j seeing keys t <= qpos[j].
+    Qsel [B,Hq,n,d], qpos [n] ints in [0, L), K [B,Hkv,L,d]; float64.  Returns [B,Hq,L]."""
+    K = np.asarray(K, dtype=np.float64)
+    Qsel = np.asarray(Qsel, dtype=np.float64)
+    qpos = np.asarray(qpos, dtype=np.int64)
+    B, Hkv, L, d = K.shape
+    Hq, n = Qsel.shape[1], Qsel.shape[2]
+    assert Qsel.shape == (B, Hq, n, d) and qpos.shape == (n,) and Hq % Hkv == 0
+    assert qpos.min() >= 0 and qpos.max() < L
+    g = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    visible = np.arange(L)[None, :] <= qpos[:, None]      # [n, L]
+    s = np.zeros((B, Hq, L), dtype=np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            x = np.where(visible, scale * (Qsel[b, h] @ K[b, h // g].T), -np.inf)
+            e = np.exp(x - x.max(axis=1, keepdims=True))
+            s[b, h] = (e / e.sum(axis=1, keepdims=True)).sum(axis=0)
+    return s
+
+
+def pool_queries(Q_bits: np.ndarray, n_pool: int):
+    """Query-only pooling of the scoring ablation: the L query rows of every head are cut into
+    n_pool contiguous segments, segment j = rows floor(j L / n_pool) .. ceil((j+1) L / n_pool) - 1
+    (the segments of adaptive average pooling), and averaged.  Q_bits [B,Hq,L,d] bf16 bit patterns.
+    Returns (pooled rows as bf16 bits [B,Hq,n_pool,d], qpos [n_pool] = last row of each segment:
+    a pooled query sees the keys its last member sees)."""
+    B, Hq, L, d = Q_bits.shape
+    assert 1 <= n_pool <= L
+    Q = bf16_to_f64(Q_bits)
+    out = np.zeros((B, Hq, n_pool, d), dtype=np.float64)
+    qpos = np.zeros(n_pool, dtype=np.int64)
+    for j in range(n_pool):
+        lo = (j * L) // n_pool
+        hi = -((-(j + 1) * L) // n_pool)
+        out[:, :, j] = Q[:, :, lo:hi].sum(axis=2) / (hi - lo)
+        qpos[j] = hi - 1
+    return f64_to_bf16(out), qpos
+
+
 def pool(s: np.ndarray, pool_w: int) -> np.ndarray:
     """Average pooling of width `pool_w` (odd), stride 1, zero padded, along t."""
     if pool_w == 1:

@@ -15,6 +15,7 @@ from . import build as _build
 TSA_OK, TSA_ERR_ARG, TSA_ERR_UNSUPPORTED, TSA_ERR_WORKSPACE, TSA_ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_bytes", "tsa_score", "tsa_coverage_budget",
+           "tsa_score_queries", "tsa_gather_queries", "tsa_pool_queries_workspace_bytes", "tsa_pool_queries",
            "tsa_select", "tsa_compress", "tsa_attend_workspace_bytes", "tsa_attend", "tsa_decompress", "tsa_compress_v_tiles", "tsa_attend_fused", "tsa_forward",
            "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe")
 
@@ -63,6 +64,15 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_workspace_bytes.argtypes = [dp, i32]
     lib.tsa_score.restype = ctypes.c_int
     lib.tsa_score.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+    ip = ctypes.POINTER(i32)
+    lib.tsa_score_queries.restype = ctypes.c_int
+    lib.tsa_score_queries.argtypes = [dp, vp, ip, i32, vp, vp, vp, sz, vp]
+    lib.tsa_gather_queries.restype = ctypes.c_int
+    lib.tsa_gather_queries.argtypes = [dp, vp, ip, i32, vp, vp]
+    lib.tsa_pool_queries_workspace_bytes.restype = sz
+    lib.tsa_pool_queries_workspace_bytes.argtypes = [dp, i32]
+    lib.tsa_pool_queries.restype = ctypes.c_int
+    lib.tsa_pool_queries.argtypes = [dp, vp, i32, vp, ip, vp, sz, vp]
     lib.tsa_coverage_budget.restype = ctypes.c_int
     lib.tsa_coverage_budget.argtypes = [dp, vp, ctypes.c_double, vp, vp, sz, vp]
     lib.tsa_select.restype = ctypes.c_int
@@ -137,6 +147,32 @@ def tsa_workspace_bytes(desc: tsa_desc, k_keep: int) -> int:
 def tsa_score(desc, Q, K, scores, ws):
     p, n = _ws(ws)
     _check(load_library().tsa_score(ctypes.byref(desc), _ptr(Q), _ptr(K), _ptr(scores), p, n, _stream()))
+
+
+def _host_ints(values):
+    return (ctypes.c_int32 * len(values))(*[int(v) for v in values])
+
+
+def tsa_score_queries(desc, Qsel, qpos, K, scores, ws):
+    """qpos: sequence of host ints (ascending positions of the rows of Qsel)."""
+    p, n = _ws(ws)
+    _check(load_library().tsa_score_queries(ctypes.byref(desc), _ptr(Qsel), _host_ints(qpos), len(qpos), _ptr(K),
+                                            _ptr(scores), p, n, _stream()))
+
+
+def tsa_gather_queries(desc, Q, qpos, Qsel):
+    _check(load_library().tsa_gather_queries(ctypes.byref(desc), _ptr(Q), _host_ints(qpos), len(qpos), _ptr(Qsel), _stream()))
+
+
+def tsa_pool_queries(desc, Q, n_pool, Qsel, ws=None):
+    """Returns the positions (host list) of the pooled queries."""
+    if ws is None:
+        ws = torch.empty(max(256, load_library().tsa_pool_queries_workspace_bytes(ctypes.byref(desc), n_pool)),
+                         dtype=torch.uint8, device=Q.device)
+    p, n = _ws(ws)
+    qpos = (ctypes.c_int32 * n_pool)()
+    _check(load_library().tsa_pool_queries(ctypes.byref(desc), _ptr(Q), n_pool, _ptr(Qsel), qpos, p, n, _stream()))
+    return list(qpos)
 
 
 def tsa_coverage_budget(desc, scores, tau_cov, k_keep, ws):

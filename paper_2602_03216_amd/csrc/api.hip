@@ -136,6 +136,59 @@ int tsa_score(const tsa_desc* desc, const void* Q, const void* K, float* scores,
   return hip_status(tsa::launch_score(dm, Q, K, scores, ws, (hipStream_t)stream), "tsa_score");
 }
 
+namespace {
+int check_positions(const int32_t* qpos, int32_t n, int32_t L) {
+  if (!qpos) return fail(TSA_ERR_ARG, "qpos is NULL");
+  for (int32_t i = 0; i < n; ++i) {
+    if (qpos[i] < 0 || qpos[i] >= L) return fail(TSA_ERR_ARG, "qpos[%d] = %d is outside [0, L)", i, qpos[i]);
+    if (i > 0 && qpos[i] < qpos[i - 1]) return fail(TSA_ERR_ARG, "qpos must be ascending");
+  }
+  return TSA_OK;
+}
+}  // namespace
+
+int tsa_score_queries(const tsa_desc* desc, const void* Qsel, const int32_t* qpos, int32_t n, const void* K,
+                      float* scores, void* ws, size_t ws_bytes, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm))) return rc;
+  if (n != dm.last_q) return fail(TSA_ERR_ARG, "n (%d) must equal desc.last_q (%d)", n, dm.last_q);
+  if ((rc = check_positions(qpos, n, dm.L))) return rc;
+  if ((rc = check_ptr(Qsel, "Qsel")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(scores, "scores"))) return rc;
+  if ((rc = check_ws(ws, ws_bytes, tsa::score_ws_bytes(dm)))) return rc;
+  return hip_status(tsa::launch_score_queries(dm, Qsel, qpos, K, scores, ws, (hipStream_t)stream), "tsa_score_queries");
+}
+
+int tsa_gather_queries(const tsa_desc* desc, const void* Q, const int32_t* qpos, int32_t n, void* Qsel, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm))) return rc;
+  if (n < 1 || n > 128) return fail(TSA_ERR_ARG, "n (%d) must lie in [1, 128]", n);
+  if ((rc = check_positions(qpos, n, dm.L))) return rc;
+  if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(Qsel, "Qsel"))) return rc;
+  return hip_status(tsa::launch_gather_queries(dm, Q, qpos, n, Qsel, (hipStream_t)stream), "tsa_gather_queries");
+}
+
+size_t tsa_pool_queries_workspace_bytes(const tsa_desc* desc, int32_t n_pool) {
+  tsa::Dims dm;
+  if (check_desc(desc, &dm) != TSA_OK) return 0;
+  if (n_pool < 1 || n_pool > 128 || n_pool > dm.L) return 0;
+  return tsa::pool_queries_ws_bytes(dm, n_pool);
+}
+
+int tsa_pool_queries(const tsa_desc* desc, const void* Q, int32_t n_pool, void* Qsel, int32_t* qpos,
+                     void* ws, size_t ws_bytes, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm))) return rc;
+  if (n_pool < 1 || n_pool > 128 || n_pool > dm.L) return fail(TSA_ERR_ARG, "n_pool (%d) must lie in [1, min(L, 128)]", n_pool);
+  if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(Qsel, "Qsel"))) return rc;
+  if ((rc = check_ws(ws, ws_bytes, tsa::pool_queries_ws_bytes(dm, n_pool)))) return rc;
+  if (qpos)
+    for (int32_t j = 0; j < n_pool; ++j) qpos[j] = (int32_t)((((long long)(j + 1)) * dm.L + n_pool - 1) / n_pool) - 1;
+  return hip_status(tsa::launch_pool_queries(dm, Q, n_pool, Qsel, ws, (hipStream_t)stream), "tsa_pool_queries");
+}
+
 int tsa_coverage_budget(const tsa_desc* desc, const float* scores, double tau_cov, int32_t* k_keep,
                         void* ws, size_t ws_bytes, void* stream) {
   tsa::Dims dm;

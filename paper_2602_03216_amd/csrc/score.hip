@@ -25,8 +25,14 @@ constexpr int kMinChunk = 1024;              // keys per workgroup: at least thi
 constexpr int kTK = 128;                     // keys per staged K tile
 constexpr float kNegBig = -1.0e30f;
 
+constexpr int kMaxQueries = 128;
+
 struct ScoreArgs {
-  const __bf16* Q;
+  const __bf16* Q;             // scoring queries: row i of head bh at Q + bh * q_head_stride + (q_row0 + i) * d
+  long long q_head_stride;
+  int q_row0;
+  int min_pos;                 // smallest entry of qpos
+  int qpos[kMaxQueries];       // position of scoring query i (ascending; query i sees keys t <= qpos[i]); padded with L - 1
   const __bf16* K;
   float* scores;
   float2* part;       // [B*Hq][nchunks][QP] (max, sum) in the log2 domain
@@ -39,12 +45,11 @@ struct ScoreArgs {
 
 template <int D, int NQT>
 __device__ __forceinline__ void load_q_frags(const ScoreArgs& a, long long bh, int lo, int hi, bf16x8 (&qf)[NQT][D / 16]) {
-  const int first = a.L - a.Lq;
 #pragma unroll
   for (int qt = 0; qt < NQT; ++qt) {
     const int qi = 32 * qt + lo;
     const bool ok = qi < a.Lq;
-    const __bf16* row = a.Q + ((bh * a.L) + (ok ? first + qi : 0)) * (long long)D + 8 * hi;
+    const __bf16* row = a.Q + bh * a.q_head_stride + (long long)(a.q_row0 + (ok ? qi : 0)) * D + 8 * hi;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
       bf16x8 v = *(const bf16x8*)(row + 16 * s);
@@ -107,10 +112,12 @@ __global__ __launch_bounds__(kThreads) void score_pass1(ScoreArgs a) {
   const long long b = bkv / a.Hkv;
   const int g = a.Hq / a.Hkv;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
-  const int first = a.L - a.Lq;
   const WaveRole role = wave_role(g, wave);
   const int c_begin = chunk * a.chunk, c_end = min(c_begin + a.chunk, a.L);
   const int sub_per_tile = (kTK / 32) / role.ksplit;     // 32-key sub-tiles of a staged tile per wavefront
+  int my_pos[NQT];                                       // position of this lane's query in each query sub-tile
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) my_pos[qt] = a.qpos[32 * qt + lo];
   KStage<D> stg;
   stg.Kh = a.K + (bkv * (long long)a.L) * D;
   stg.L = a.L; stg.st_row = tid / (D / 8); stg.st_col = tid % (D / 8);
@@ -136,7 +143,7 @@ __global__ __launch_bounds__(kThreads) void score_pass1(ScoreArgs a) {
           const int sub = role.kpart * sub_per_tile + sb;
           const int t0 = k0 + 32 * sub;
           if (t0 >= a.L) break;
-          const bool need_mask = t0 + 31 > first;      // sub-tile reaches into the window or past L
+          const bool need_mask = t0 + 31 > a.min_pos;  // some query cannot see the whole sub-tile, or it runs past L
 #pragma unroll
           for (int qt = 0; qt < NQT; ++qt) {
             f32x16 acc = {0};
@@ -145,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void score_pass1(ScoreArgs a) {
               const bf16x8 kf = *(const bf16x8*)(&Ks[par][32 * sub * KS + k_rd + 16 * s]);
               acc = mfma32(kf, qf[qt][s], acc);        // rows = keys, cols = queries
             }
-            const int qpos = first + 32 * qt + lo;     // position of this lane's query
+            const int qpos = my_pos[qt];
             if (need_mask) {
 #pragma unroll
               for (int r = 0; r < 16; ++r) {
@@ -226,7 +233,6 @@ __global__ __launch_bounds__(kThreads) void score_pass2(ScoreArgs a) {
   const long long b = bkv / a.Hkv;
   const int g = a.Hq / a.Hkv;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
-  const int first = a.L - a.Lq;
   const WaveRole role = wave_role(g, wave);
   const int c_begin = chunk * a.chunk, c_end = min(c_begin + a.chunk, a.L);
   const int sub_per_tile = (kTK / 32) / role.ksplit;
@@ -260,7 +266,18 @@ __global__ __launch_bounds__(kThreads) void score_pass2(ScoreArgs a) {
           const int t0 = k0 + 32 * sub;
           if (t0 >= a.L) break;
           const int t = t0 + lo;                       // this lane's key
-          const bool need_mask = t0 + 31 > first;
+          const bool need_mask = t0 + 31 > a.min_pos;
+          // Queries are in ascending position order: key t is hidden from exactly the queries with
+          // index < n_hidden = #{i : qpos[i] < t} (binary search in the position table).
+          int n_hidden = 0;
+          if (need_mask) {
+            int lo_i = 0, hi_i = QP;
+            while (lo_i < hi_i) {
+              const int mid = (lo_i + hi_i) >> 1;
+              if (a.qpos[mid] < t) lo_i = mid + 1; else hi_i = mid;
+            }
+            n_hidden = lo_i;
+          }
           float colsum = 0.f;
 #pragma unroll
           for (int qt = 0; qt < NQT; ++qt) {
@@ -273,10 +290,7 @@ __global__ __launch_bounds__(kThreads) void score_pass2(ScoreArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
               float p = fast_exp2(acc[r] * a.c - lse[qt][r]);
-              if (need_mask) {
-                const int qpos = first + 32 * qt + c_row(r, hi);
-                if (t > qpos) p = 0.f;
-              }
+              if (32 * qt + c_row(r, hi) < n_hidden) p = 0.f;
               colsum += p;
             }
           }
@@ -341,11 +355,12 @@ size_t score_ws_bytes(const Dims& dm) {
          (dm.pool_w > 1 ? align256(BH * dm.L * sizeof(float)) : 0);
 }
 
-hipError_t launch_score(const Dims& dm, const void* Q, const void* K, float* scores, void* ws, hipStream_t st) {
+namespace {
+
+hipError_t launch_common(const Dims& dm, ScoreArgs& a, const void* K, float* scores, void* ws, hipStream_t st) {
   const int nqt = nqt_for(dm.last_q);
   const int QP = 32 * nqt;
-  ScoreArgs a;
-  a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.scores = scores;
+  a.K = (const __bf16*)K; a.scores = scores;
   a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.L = dm.L; a.Lq = dm.last_q;
   a.chunk = chunk_for(dm);
   a.nchunks = (dm.L + a.chunk - 1) / a.chunk;
@@ -368,6 +383,139 @@ hipError_t launch_score(const Dims& dm, const void* Q, const void* K, float* sco
   if (nqt == 1) return run<64, 1>(a, bh, st);
   if (nqt == 2) return run<64, 2>(a, bh, st);
   return run<64, 4>(a, bh, st);
+}
+
+}  // namespace
+
+// Algorithm 1's scorer: the last last_q rows of Q at their own positions.
+hipError_t launch_score(const Dims& dm, const void* Q, const void* K, float* scores, void* ws, hipStream_t st) {
+  ScoreArgs a;
+  a.Q = (const __bf16*)Q;
+  a.q_head_stride = (long long)dm.L * dm.d;
+  a.q_row0 = dm.L - dm.last_q;
+  a.min_pos = dm.L - dm.last_q;
+  for (int i = 0; i < kMaxQueries; ++i) a.qpos[i] = i < dm.last_q ? dm.L - dm.last_q + i : dm.L - 1;
+  return launch_common(dm, a, K, scores, ws, st);
+}
+
+// Scoring from caller-supplied query rows Qsel [B,Hq,last_q,d] at positions qpos (host, ascending).
+hipError_t launch_score_queries(const Dims& dm, const void* Qsel, const int32_t* qpos, const void* K, float* scores,
+                                void* ws, hipStream_t st) {
+  ScoreArgs a;
+  a.Q = (const __bf16*)Qsel;
+  a.q_head_stride = (long long)dm.last_q * dm.d;
+  a.q_row0 = 0;
+  a.min_pos = qpos[0];
+  for (int i = 0; i < kMaxQueries; ++i) a.qpos[i] = i < dm.last_q ? qpos[i] : dm.L - 1;
+  return launch_common(dm, a, K, scores, ws, st);
+}
+
+// ---- the query sets of the scoring ablation
+
+namespace {
+
+struct GatherArgs {
+  const u32x4* Q;
+  u32x4* Qsel;
+  int L, n, lpr;               // lpr = 16-byte pieces per row
+  int qpos[kMaxQueries];
+};
+
+// Qsel[bh, j, :] = Q[bh, qpos[j], :]
+__global__ void gather_queries_kernel(GatherArgs a, long long n_pieces) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_pieces) return;
+  const int piece = (int)(i % a.lpr);
+  const long long row = i / a.lpr;
+  const int j = (int)(row % a.n);
+  const long long bh = row / a.n;
+  a.Qsel[i] = a.Q[(bh * a.L + a.qpos[j]) * a.lpr + piece];
+}
+
+// Segment j of the query-only pooling: rows floor(j L / n) .. ceil((j+1) L / n) - 1.
+__device__ __forceinline__ void segment(int j, int L, int n, int& lo, int& hi) {
+  lo = (int)(((long long)j * L) / n);
+  hi = (int)((((long long)(j + 1)) * L + n - 1) / n);
+}
+
+// Stage 1: workgroup (split s, segment j, head bh) adds its slice of the segment's rows, thread = one
+// d-column pair... one thread per 2 columns would leave most lanes idle at d = 128, so a thread
+// owns 8 columns (16 bytes) and kPoolRows threads share a column group; they are folded in LDS.
+constexpr int kPoolThreads = 256;
+template <int D>
+__global__ __launch_bounds__(kPoolThreads) void pool_queries_partial(const u32x4* __restrict__ Q, float* __restrict__ part,
+                                                                     int L, int n_pool, int n_split) {
+  constexpr int LPR = D / 8, RPP = kPoolThreads / LPR;      // rows per pass
+  __shared__ float red[RPP][D];
+  const int s = blockIdx.x, j = blockIdx.y;
+  const long long bh = blockIdx.z;
+  int lo, hi;
+  segment(j, L, n_pool, lo, hi);
+  const int len = hi - lo, per = (len + n_split - 1) / n_split;
+  const int r_begin = lo + s * per, r_end = min(hi, r_begin + per);
+  const int piece = threadIdx.x % LPR, rr = threadIdx.x / LPR;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int r = r_begin + rr; r < r_end; r += RPP) {
+    const u32x4 v = Q[(bh * L + r) * LPR + piece];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      acc[2 * c] += __uint_as_float(v[c] << 16);
+      acc[2 * c + 1] += __uint_as_float(v[c] & 0xffff0000u);
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < 8; ++c) red[rr][8 * piece + c] = acc[c];
+  __syncthreads();
+  if (threadIdx.x < D) {
+    float t = 0.f;
+    for (int r = 0; r < RPP; ++r) t += red[r][threadIdx.x];                 // fixed order: deterministic
+    part[((bh * n_pool + j) * n_split + s) * D + threadIdx.x] = t;
+  }
+}
+
+// Stage 2: mean of the segment, rounded to bf16.
+__global__ void pool_queries_final(const float* __restrict__ part, __bf16* __restrict__ Qsel, int L, int n_pool, int n_split,
+                                   int D, long long n) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int c = (int)(i % D);
+  const long long seg = i / D;                               // bh * n_pool + j
+  int lo, hi;
+  segment((int)(seg % n_pool), L, n_pool, lo, hi);
+  float t = 0.f;
+  for (int s = 0; s < n_split; ++s) t += part[(seg * n_split + s) * D + c];
+  Qsel[i] = (__bf16)(t / (float)(hi - lo));
+}
+
+inline int pool_split(int L, int n_pool) {
+  const int max_len = (L + n_pool - 1) / n_pool + 1;
+  int s = (max_len + 1023) / 1024;
+  return s < 1 ? 1 : (s > 64 ? 64 : s);
+}
+
+}  // namespace
+
+hipError_t launch_gather_queries(const Dims& dm, const void* Q, const int32_t* qpos, int n, void* Qsel, hipStream_t st) {
+  GatherArgs a;
+  a.Q = (const u32x4*)Q; a.Qsel = (u32x4*)Qsel; a.L = dm.L; a.n = n; a.lpr = dm.d / 8;
+  for (int i = 0; i < kMaxQueries; ++i) a.qpos[i] = i < n ? qpos[i] : 0;
+  const long long pieces = (long long)dm.B * dm.Hq * n * a.lpr;
+  gather_queries_kernel<<<(unsigned)((pieces + 255) / 256), 256, 0, st>>>(a, pieces);
+  return hipGetLastError();
+}
+
+size_t pool_queries_ws_bytes(const Dims& dm, int n_pool) {
+  return align256((size_t)dm.B * dm.Hq * n_pool * pool_split(dm.L, n_pool) * dm.d * sizeof(float));
+}
+
+hipError_t launch_pool_queries(const Dims& dm, const void* Q, int n_pool, void* Qsel, void* ws, hipStream_t st) {
+  const int n_split = pool_split(dm.L, n_pool);
+  const dim3 grid((unsigned)n_split, (unsigned)n_pool, (unsigned)(dm.B * dm.Hq));
+  if (dm.d == 128) pool_queries_partial<128><<<grid, kPoolThreads, 0, st>>>((const u32x4*)Q, (float*)ws, dm.L, n_pool, n_split);
+  else pool_queries_partial<64><<<grid, kPoolThreads, 0, st>>>((const u32x4*)Q, (float*)ws, dm.L, n_pool, n_split);
+  const long long n = (long long)dm.B * dm.Hq * n_pool * dm.d;
+  pool_queries_final<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((const float*)ws, (__bf16*)Qsel, dm.L, n_pool, n_split, dm.d, n);
+  return hipGetLastError();
 }
 
 }  // namespace tsa

@@ -43,6 +43,12 @@ struct Dims {
 size_t score_ws_bytes(const Dims& dm);
 hipError_t launch_score(const Dims& dm, const void* Q, const void* K, float* scores, void* ws, hipStream_t st);
 
+hipError_t launch_score_queries(const Dims& dm, const void* Qsel, const int32_t* qpos_host, const void* K, float* scores,
+                                void* ws, hipStream_t st);
+hipError_t launch_gather_queries(const Dims& dm, const void* Q, const int32_t* qpos_host, int n, void* Qsel, hipStream_t st);
+size_t pool_queries_ws_bytes(const Dims& dm, int n_pool);
+hipError_t launch_pool_queries(const Dims& dm, const void* Q, int n_pool, void* Qsel, void* ws, hipStream_t st);
+
 // select.hip
 size_t select_ws_bytes(const Dims& dm);
 hipError_t launch_select(const Dims& dm, const float* scores, int k_keep, int32_t* idx, int32_t* inv,

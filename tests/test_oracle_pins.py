@@ -136,6 +136,44 @@ def test_score_window_is_causal():
     assert abs(s[0, 0, L - 2] - scipy.special.softmax(logits)[L - 2] - scipy.special.softmax(l2)[L - 2]) < 1e-14
 
 
+def test_score_queries_reduces_to_recent_query_scoring_and_brute_force():
+    r = _rng(61)
+    B, Hq, Hkv, L, d, n = 2, 4, 2, 37, 8, 5
+    Q, K = r.standard_normal((B, Hq, L, d)), r.standard_normal((B, Hkv, L, d))
+    # the most recent queries at their own positions: Algorithm 1's scorer
+    assert np.allclose(orc.score_queries(Q[:, :, L - n:], np.arange(L - n, L), K), orc.score(Q, K, n), rtol=0, atol=1e-14)
+    # arbitrary positions against a pure-Python loop
+    qpos = np.array([3, 0, 36, 17, 17])
+    Qs = Q[:, :, qpos]
+    got = orc.score_queries(Qs, qpos, K, scale=0.3)
+    for b in range(B):
+        for h in range(Hq):
+            want = [0.0] * L
+            for j, pj in enumerate(qpos):
+                w = [math.exp(0.3 * sum(Qs[b, h, j, c] * K[b, h // 2, t, c] for c in range(d))) for t in range(pj + 1)]
+                z = sum(w)
+                for t in range(pj + 1):
+                    want[t] += w[t] / z
+            assert np.allclose(got[b, h], want, rtol=0, atol=1e-13)
+    assert np.allclose(got.sum(-1), n)                     # every query distributes a mass of one
+
+
+def test_pool_queries_matches_adaptive_average_pooling():
+    r = _rng(62)
+    B, Hq, L, d = 1, 2, 53, 8
+    from paper_2602_03216_amd import inputs as gen
+    Qb = gen.f32_to_bf16_bits(r.standard_normal((B, Hq, L, d)).astype(np.float32))
+    Qf = torch.from_numpy(orc.bf16_to_f64(Qb))
+    for n_pool in (1, 4, 7, 53):
+        bits, qpos = orc.pool_queries(Qb, n_pool)
+        ref = torch.nn.functional.adaptive_avg_pool1d(Qf.reshape(B * Hq, L, d).transpose(1, 2), n_pool).transpose(1, 2)
+        ref_bits = torch.from_numpy(ref.reshape(B, Hq, n_pool, d).numpy().astype(np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        assert np.array_equal(bits, ref_bits)
+        assert qpos[-1] == L - 1 and all(qpos[j] < qpos[j + 1] for j in range(n_pool - 1))
+    assert orc.pool_queries(Qb, 1)[1].tolist() == [L - 1]   # a single pooled query sees every key
+    assert np.array_equal(orc.pool_queries(Qb, L)[0], Qb)   # one row per segment: the rows themselves
+
+
 def test_pool_average_zero_padded():
     s = np.array([[1.0, 2.0, 4.0, 8.0, 16.0]])
     assert np.array_equal(orc.pool(s, 1), s)
