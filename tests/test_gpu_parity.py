@@ -265,21 +265,23 @@ def test_forward_small(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant):
     assert not gu.from_dev(O)[np.repeat(~sel, Hq // Hs, axis=1)].any()
 
 
-@pytest.mark.parametrize("Hq,Hkv,L,d,k,group_mode,with_blocks", [
-    (4, 2, 1500, 128, 700, 0, False),
-    (6, 2, 1203, 128, 333, 1, False),
-    (4, 4, 900, 64, 900, 0, False),
-    (4, 2, 2100, 128, 1100, 0, True),
+@pytest.mark.parametrize("B,Hq,Hkv,L,d,k,group_mode,with_blocks", [
+    (1, 4, 2, 1500, 128, 700, 0, False),
+    (2, 6, 2, 1203, 128, 333, 1, False),
+    (1, 4, 4, 900, 64, 900, 0, False),
+    (1, 4, 2, 2100, 128, 1100, 0, True),
+    (3, 2, 1, 777, 64, 200, 0, True),
+    (2, 4, 2, 520, 128, 1, 0, False),
 ])
-def test_fused_path_equals_the_separate_calls(tsa, Hq, Hkv, L, d, k, group_mode, with_blocks):
+def test_fused_path_equals_the_separate_calls(tsa, B, Hq, Hkv, L, d, k, group_mode, with_blocks):
     """tsa_forward / tsa_compress_v_tiles + tsa_attend_fused against tsa_score -> tsa_select ->
     tsa_compress -> tsa_attend -> tsa_decompress on the same inputs: gather and scatter are copies
     and the arithmetic is the same, so every output must match bit for bit (the separate calls are
     the ones checked against the oracle above)."""
     r = _rng(900 + L)
     Lq = 64
-    Q, K, V = (gu.to_dev(gu.rand_bits(r, (1, h, L, d))) for h in (Hq, Hkv, Hkv))
-    desc = tsa.make_desc(1, Hq, Hkv, L, d, Lq, group_mode=group_mode)
+    Q, K, V = (gu.to_dev(gu.rand_bits(r, (B, h, L, d))) for h in (Hq, Hkv, Hkv))
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq, group_mode=group_mode)
     Hs = Hkv if group_mode else Hq
     ws = _ws(tsa, desc, k)
     bl = bl_kw = None
@@ -288,12 +290,12 @@ def test_fused_path_equals_the_separate_calls(tsa, Hq, Hkv, L, d, k, group_mode,
         bl = torch.from_numpy(orc.lambda_block_list(k, 128, 256, 1)).to(gu.DEV)
         kw = dict(block_list=bl, block_size=128, max_blocks_per_row=bl.shape[1])
     # separate calls
-    s = torch.empty((1, Hq, L), dtype=torch.float32, device=gu.DEV)
-    idx = torch.empty((1, Hs, k), dtype=torch.int32, device=gu.DEV)
-    inv = torch.empty((1, Hs, L), dtype=torch.int32, device=gu.DEV)
-    Qc = torch.empty((1, Hq, k, d), dtype=torch.bfloat16, device=gu.DEV)
-    Kc = torch.empty((1, Hs, k, d), dtype=torch.bfloat16, device=gu.DEV)
-    Vc, Oc, O1 = torch.empty_like(Kc), torch.empty_like(Qc), torch.full((1, Hq, L, d), 5.0, dtype=torch.bfloat16, device=gu.DEV)
+    s = torch.empty((B, Hq, L), dtype=torch.float32, device=gu.DEV)
+    idx = torch.empty((B, Hs, k), dtype=torch.int32, device=gu.DEV)
+    inv = torch.empty((B, Hs, L), dtype=torch.int32, device=gu.DEV)
+    Qc = torch.empty((B, Hq, k, d), dtype=torch.bfloat16, device=gu.DEV)
+    Kc = torch.empty((B, Hs, k, d), dtype=torch.bfloat16, device=gu.DEV)
+    Vc, Oc, O1 = torch.empty_like(Kc), torch.empty_like(Qc), torch.full((B, Hq, L, d), 5.0, dtype=torch.bfloat16, device=gu.DEV)
     tsa.tsa_score(desc, Q, K, s, ws)
     tsa.tsa_select(desc, s, k, idx, inv, ws)
     tsa.tsa_compress(desc, Q, K, V, idx, k, Qc, Kc, Vc)
