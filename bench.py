@@ -139,7 +139,7 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
     return out, inp
 
 
-def cpu_baseline(inp, k, budget_rows=2048):
+def cpu_baseline(inp, k, budget_rows=4096):
     """The CPU oracle, as it stands, on a bounded sample of the headline workload: scoring and
     selection in full; compression, attention and decompression for a few heads / rows, scaled
     to the whole layer (the scaling is by rows x keys actually computed)."""
@@ -155,7 +155,7 @@ def cpu_baseline(inp, k, budget_rows=2048):
     idx, inv = orc.select(s, k)
     t_select = time.perf_counter() - t0
     # attention on sampled compacted rows of two heads; cost model: time per (row, visible key) pair
-    heads = sorted(set(range(0, Hq, max(1, Hq // 8))))
+    heads = sorted(set(range(0, Hq, max(1, Hq // 16))))
     rows = np.unique(np.linspace(0, k - 1, budget_rows).astype(np.int64))
     t_gather = t_att = 0.0
     pairs = 0
