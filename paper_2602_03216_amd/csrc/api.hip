@@ -39,6 +39,8 @@ int check_desc(const tsa_desc* d, tsa::Dims* out) {
     return fail(TSA_ERR_ARG, "force_first / force_last out of range");
   if (!(d->scale >= 0.0f) || !std::isfinite(d->scale)) return fail(TSA_ERR_ARG, "scale must be finite and >= 0");
   if ((long long)d->B * d->Hq > 65535) return fail(TSA_ERR_UNSUPPORTED, "B*Hq > 65535");
+  // one head of Q / K / V / inv is addressed with 32-bit byte offsets inside the kernels
+  if ((long long)d->L * d->d * 2 >= (1LL << 31)) return fail(TSA_ERR_UNSUPPORTED, "L (%d) too long: one head must stay below 2 GiB", d->L);
   out->B = d->B; out->Hq = d->Hq; out->Hkv = d->Hkv; out->L = d->L; out->d = d->d;
   out->last_q = d->last_q; out->pool_w = d->pool_w; out->group_mode = d->group_mode;
   out->force_first = d->force_first; out->force_last = d->force_last;
@@ -237,6 +239,7 @@ int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void*
   int rc;
   if ((rc = check_desc(desc, &dm))) return rc;
   if (Lc < 1) return fail(TSA_ERR_ARG, "Lc (%d) must be >= 1", Lc);
+  if ((long long)Lc * dm.d * 2 >= (1LL << 31)) return fail(TSA_ERR_UNSUPPORTED, "Lc (%d) too long: one head must stay below 2 GiB", Lc);
   if (kv_heads < 1 || dm.Hq % kv_heads != 0) return fail(TSA_ERR_ARG, "kv_heads (%d) must divide Hq (%d)", kv_heads, dm.Hq);
   if ((rc = check_ptr(Qc, "Qc")) || (rc = check_ptr(Kc, "Kc")) || (rc = check_ptr(Vc, "Vc")) || (rc = check_ptr(Oc, "Oc")))
     return rc;

@@ -48,6 +48,8 @@ def test_workspace_bytes(lib):
     assert tsa.tsa_workspace_bytes(tsa.make_desc(1, 32, 7, 1024, 128), 16) == 0
     assert "multiple" in tsa.tsa_last_error()
     assert tsa.tsa_workspace_bytes(tsa.make_desc(1, 4, 4, 1024, 96), 16) == 0
+    assert tsa.tsa_workspace_bytes(tsa.make_desc(1, 1, 1, 1 << 23, 128), 16) == 0      # a head of 2 GiB: 32-bit offsets end here
+    assert tsa.tsa_workspace_bytes(tsa.make_desc(1, 1, 1, (1 << 23) - 1, 128), 16) > 0
     assert tsa.tsa_workspace_bytes(tsa.make_desc(1, 4, 4, 32, 64, last_q=64), 16) == 0
     g1 = tsa.tsa_workspace_bytes(tsa.make_desc(1, 32, 8, 4096, 128, group_mode=1), 1024)
     g0 = tsa.tsa_workspace_bytes(tsa.make_desc(1, 32, 8, 4096, 128, group_mode=0), 1024)
