@@ -155,3 +155,57 @@ def test_workload5_interleaved_stack(tsa):
         assert torch.equal(x[0, tok_check], want)
         print("stack layer %d: max|dO| %.4g mean|dO| %.4g margin %.3g" % (layer, err[0], err[1], margin), flush=True)
         del Q, K, V, O
+
+
+def _long_head(L, d, seed, tensor):
+    """One head of N(0,1) values as float32, drawn in 64 independent seeded chunks by a thread pool
+    (the workload generator draws a head from a single stream, too slow for millions of rows)."""
+    from concurrent.futures import ThreadPoolExecutor
+    out = np.empty((L, d), dtype=np.float32)
+    bounds = np.linspace(0, L, 65).astype(np.int64)
+
+    def fill(c):
+        rng = np.random.Generator(np.random.PCG64([seed, tensor, c]))
+        rng.standard_normal(out=out[bounds[c]:bounds[c + 1]], dtype=np.float32)
+
+    with ThreadPoolExecutor(max_workers=16) as pool:
+        list(pool.map(fill, range(64)))
+    return out
+
+
+def test_long_sequence_offsets_beyond_2_to_30(tsa):
+    """One head of 4.3 million tokens (1.1 GB per tensor: byte offsets inside a head pass 2^30, token
+    ids pass 2^22), ragged length.  2000 tokens are planted with a logit boost of 12 nats (the
+    workload generator's "direction" recipe: queries and planted keys get + c u), far above the
+    largest of the other four million scores, so the index set is unambiguous without any margin
+    procedure; the whole compacted attention and every zero row are checked."""
+    L, d, Lq, k = 4_300_011, 128, 64, 2000
+    r = np.random.Generator(np.random.PCG64(4242))
+    u = r.standard_normal(d).astype(np.float32)
+    u /= np.linalg.norm(u)
+    c = np.float32(np.sqrt(12.0 * np.sqrt(d)))
+    planted = np.sort(r.choice(L - Lq, size=k, replace=False))
+    Qf, Kf, Vf = (_long_head(L, d, 4242, t) for t in (1, 2, 3))
+    Qf += c * u
+    Kf[planted] += c * u
+    # rounding to bf16 by torch (nearest even, the same rounding as the generator's; multi-threaded)
+    Qb, Kb, Vb = (torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)[None, None] for x in (Qf, Kf, Vf))
+    del Qf, Kf, Vf
+    desc = tsa.make_desc(1, 1, 1, L, d, Lq)
+    Q, K, V = gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb)
+    O = torch.full((1, 1, L, d), 2.0, dtype=torch.bfloat16, device=gu.DEV)
+    idx = torch.zeros((1, 1, k), dtype=torch.int32, device=gu.DEV)
+    tsa.tsa_forward(desc, Q, K, V, k, O, tsa.alloc_workspace(desc, k, gu.DEV), idx_out=idx)
+    torch.cuda.synchronize()
+    s_ref = orc.score(orc.bf16_to_f64(Qb[:, :, L - Lq:, :]), orc.bf16_to_f64(Kb), Lq)
+    widx, _ = orc.select(s_ref, k)
+    assert np.array_equal(planted, widx[0, 0])                  # the planted tokens are the top k, by a wide gap
+    top = np.sort(s_ref[0, 0])
+    assert top[-k] > 4.0 * top[-k - 1]
+    assert np.array_equal(idx.cpu().numpy(), widx)
+    Qc, Kc, Vc = orc.compress(Qb, Kb, Vb, widx, 0)
+    want = orc.f64_to_bf16(orc.attend(orc.bf16_to_f64(Qc), orc.bf16_to_f64(Kc), orc.bf16_to_f64(Vc)))
+    rows = O[0, 0, torch.from_numpy(widx[0, 0].astype(np.int64)).to(gu.DEV)]
+    gu.assert_output_close(rows.view(torch.int16).cpu().numpy().view(np.uint16)[None, None], want, "long-sequence forward")
+    assert int((O[0, 0].view(torch.int16) != 0).any(dim=1).sum().item()) <= k       # every other row is zero
+    assert int(widx.max()) > (1 << 22)
