@@ -27,10 +27,6 @@
 
 #include <climits>
 
-#ifndef TSA_PROBE
-#define TSA_PROBE 0   // >0: timing probes that drop parts of the softmax arithmetic (results are wrong)
-#endif
-
 namespace tsa {
 
 namespace {
@@ -521,20 +517,10 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
 #pragma unroll
             for (int e = 0; e < EPS; e += 2) {
               const int r = EPS * i + e;
-#if TSA_PROBE >= 3
-              p_out[qs][r >> 1] = __float_as_uint(s_in[qs][r]);
-              continue;
-#endif
-#if TSA_PROBE >= 1
-              const float p0 = s_in[qs][r] * c_, p1 = s_in[qs][r + 1] * c_;
-#else
               const float p0 = fast_exp2(fmaf(s_in[qs][r], c_, -m[qs]));
               const float p1 = fast_exp2(fmaf(s_in[qs][r + 1], c_, -m[qs]));
-#endif
-#if TSA_PROBE < 2
               ps0[qs] += p0;
               ps1[qs] += p1;
-#endif
               p_out[qs][r >> 1] = pack_bf16(p0, p1);
             }
             if (qs + 1 < QS) __builtin_amdgcn_sched_barrier(0);
@@ -557,16 +543,14 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
           for (int qs = 0; qs < QS; ++qs) {
             if (i == 0) mx[qs] = s_in[qs][0];
             o[qs][dt] = mfma32(vf, p_operand(pb[qs], hf), o[qs][dt]);
-#if TSA_PROBE < 2
             if (EPC == 2) mx[qs] = __builtin_fmaxf(__builtin_fmaxf(mx[qs], s_in[qs][2 * i]), s_in[qs][2 * i + 1]);
             else {
 #pragma unroll
               for (int e = 0; e < EPC; ++e) mx[qs] = fmaxf(mx[qs], s_in[qs][EPC * i + e]);
             }
-#endif
             if (qs + 1 < QS) __builtin_amdgcn_sched_barrier(0);
           }
-          if (blk == 3 && TSA_PROBE < 4) {                 // K(t+2) -> kf, V(t+1) -> vn, then refill the registers
+          if (blk == 3) {                 // K(t+2) -> kf, V(t+1) -> vn, then refill the registers
             if (i < CH) {
               *(u32x4*)(&kf[lk_off + i * kRowsPerPass * KS]) = kreg[i];
               kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, ktok[i] * ROWB + 16 * st_col, 0, 0);
@@ -585,9 +569,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
         __builtin_amdgcn_sched_barrier(0);
         if (c == 2 * CPB - 1) raise_max<ND, QS>(mxc, m, l, o);
       }
-#if TSA_PROBE < 5
       lds_barrier();
-#endif
       raise_max<ND, QS>(mxc, m, l, o);
       rotate();
     }
