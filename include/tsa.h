@@ -181,7 +181,9 @@ int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, con
  *   Q[b,h,idx[r],:], K[b,h/g,idx[r],:] (original tensors) and the V tiles; writes
  *   O [B,Hq,L,d] (may be NULL): O[b,h,idx[r],:] = output row r, every other row zero (needs inv), and/or
  *   Oc [B,Hq,k_keep,d] (may be NULL): the compacted output, as tsa_attend would.
- *   block_list as in tsa_attend. */
+ *   block_list as in tsa_attend.
+ *   idx and inv must be what tsa_select wrote (ascending sets with values in [0, L), inv their
+ *   inverse): the kernel addresses Q, K and O through them without further checks. */
 int tsa_compress_v_tiles(const tsa_desc* desc, const void* V, const int32_t* idx, int32_t k_keep,
                          void* Vt, size_t vt_bytes, void* stream);
 int tsa_attend_fused(const tsa_desc* desc, const void* Q, const void* K, const void* Vt,
