@@ -204,22 +204,30 @@ __global__ __launch_bounds__(kThreads) void score_pass1(ScoreArgs a) {
   }
 }
 
-// One thread per (head, query): fold the chunk partials into lse2 = max + log2(sum).
-// Padded queries (index >= last_q) get +inf so that pass 2 gives them weight exp2(-inf) = 0.
-__global__ void score_lse(ScoreArgs a, int QP, long long n) {
-  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+// One wavefront per (head, query): fold the chunk partials into lse2 = max + log2(sum), lanes over
+// chunks.  Padded queries (index >= last_q) get +inf so that pass 2 gives them weight exp2(-inf) = 0.
+__global__ __launch_bounds__(256) void score_lse(ScoreArgs a, int QP, long long n) {
+  const long long i = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
   if (i >= n) return;
   const int q = (int)(i % QP);
   const long long bh = i / QP;
-  if (q >= a.Lq) { a.lse2[i] = INFINITY; return; }
+  if (q >= a.Lq) {
+    if (lane == 0) a.lse2[i] = INFINITY;
+    return;
+  }
   float mn = kNegBig;
-  for (int c = 0; c < a.nchunks; ++c) mn = fmaxf(mn, a.part[(bh * a.nchunks + c) * QP + q].x);
+  for (int c = lane; c < a.nchunks; c += 64) mn = fmaxf(mn, a.part[(bh * a.nchunks + c) * QP + q].x);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mn = fmaxf(mn, __shfl_xor(mn, off));
   float zs = 0.f;
-  for (int c = 0; c < a.nchunks; ++c) {
+  for (int c = lane; c < a.nchunks; c += 64) {
     const float2 p = a.part[(bh * a.nchunks + c) * QP + q];
     zs += p.y * exp2f(p.x - mn);
   }
-  a.lse2[i] = mn + log2f(zs);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) zs += __shfl_xor(zs, off);     // butterfly: every lane ends with the same sum
+  if (lane == 0) a.lse2[i] = mn + log2f(zs);
 }
 
 template <int D, int NQT>
@@ -322,7 +330,7 @@ hipError_t run(const ScoreArgs& a, int BH, hipStream_t st) {
   dim3 grid(a.nchunks, BH / (a.Hq / a.Hkv));             // one workgroup per (KV head, chunk)
   score_pass1<D, NQT><<<grid, kThreads, 0, st>>>(a);
   const long long n = (long long)BH * QP;
-  score_lse<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(a, QP, n);
+  score_lse<<<(unsigned)((n + 3) / 4), 256, 0, st>>>(a, QP, n);
   score_pass2<D, NQT><<<grid, kThreads, 0, st>>>(a);
   if (a.pool_w > 1) {
     const long long nt = (long long)BH * a.L;
