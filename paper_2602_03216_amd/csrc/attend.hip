@@ -479,6 +479,11 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     constexpr int kPF = TSA_PF, kRing = TSA_RING, kChunks = 4 * NS;
     static_assert(NS == 8 || NS == 4, "chunk stream is laid out for d = 128 or 64");
     constexpr int CPB = kChunks / 4;                       // chunks per block
+    // slot = chunk % kRing must mean the same slot in consecutive iterations; a fragment must not be
+    // overwritten before it is consumed; and the fragments fetched across the iteration boundary
+    // must all belong to block 0 (K of the next tile, complete since the previous barrier), not to
+    // the V tile that this iteration is still writing
+    static_assert(kChunks % kRing == 0 && kRing > kPF && kPF <= CPB, "fragment ring does not fit the chunk stream");
     bf16x8 kfr[kRing];
     // fragment fetch for chunk c of the iteration whose tiles sit in (kc_, kn_, vc_)
     auto fetch = [&](int c, const __bf16* kc_, const __bf16* kn_, const __bf16* vc_) {
