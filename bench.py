@@ -86,6 +86,14 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
         t_fwd = _events_ms(fwd, steps, torch)
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3 / steps
+        # the same call recorded once into a HIP graph and replayed (no launch gaps between its kernels)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fwd()
+        graph.replay()
+        torch.cuda.synchronize()
+        t_graph = _events_ms(graph.replay, steps, torch)
+        del graph
         # the five entry points one by one, on buffers of their own
         scores = torch.empty((B, Hq, L), dtype=torch.float32, device=dev)
         idx = torch.empty((B, Hq, k), dtype=torch.int32, device=dev)
@@ -113,7 +121,7 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
             t[name] = _events_ms(fn, part_iters, torch)
         w = algorithmic_work(cfg, k)
         rec = {
-            "k_keep": k, "forward_ms": t_fwd, "forward_wall_ms": wall,
+            "k_keep": k, "forward_ms": t_fwd, "forward_wall_ms": wall, "forward_graph_replay_ms": t_graph,
             "score_ms": t["score"], "select_ms": t["select"], "compress_ms": t["compress"],
             "attend_ms": t["attend"], "decompress_ms": t["decompress"],
             "v_tiles_ms": t["v_tiles"], "attend_fused_ms": t["attend_fused"],
