@@ -180,8 +180,10 @@ int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, con
  * tsa_attend_fused: causal attention over the compacted set, reading row r of head h as
  *   Q[b,h,idx[r],:], K[b,h/g,idx[r],:] (original tensors) and the V tiles; writes
  *   O [B,Hq,L,d] (may be NULL): O[b,h,idx[r],:] = output row r, every other row zero (needs inv), and/or
- *   Oc [B,Hq,k_keep,d] (may be NULL): the compacted output, as tsa_attend would.
- *   block_list as in tsa_attend.
+ *   Oc [B,Hq,k_keep,d] (may be NULL): the compacted output, as tsa_attend would;
+ *   residual [B,L,Hq*d] (may be NULL): as in tsa_decompress, residual[b,idx[r],h*d:(h+1)*d] += output row r
+ *   (rounded to bf16 first, then added in fp32 and rounded once: bit-identical to tsa_decompress).
+ *   At least one of the three must be given.  block_list as in tsa_attend.
  *   idx and inv must be what tsa_select wrote (ascending sets with values in [0, L), inv their
  *   inverse): the kernel addresses Q, K and O through them without further checks. */
 int tsa_compress_v_tiles(const tsa_desc* desc, const void* V, const int32_t* idx, int32_t k_keep,
@@ -189,7 +191,7 @@ int tsa_compress_v_tiles(const tsa_desc* desc, const void* V, const int32_t* idx
 int tsa_attend_fused(const tsa_desc* desc, const void* Q, const void* K, const void* Vt,
                      const int32_t* idx, const int32_t* inv, int32_t k_keep,
                      const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
-                     void* O, void* Oc, void* stream);
+                     void* O, void* Oc, void* residual, void* stream);
 
 /* The whole layer on one stream, no host synchronisation:
  * score -> select -> compress -> attend -> decompress (Figure 3 of the paper).  Same results as the

@@ -84,7 +84,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_compress_v_tiles.restype = ctypes.c_int
     lib.tsa_compress_v_tiles.argtypes = [dp, vp, vp, i32, vp, sz, vp]
     lib.tsa_attend_fused.restype = ctypes.c_int
-    lib.tsa_attend_fused.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp]
+    lib.tsa_attend_fused.argtypes = [dp, vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp]
     lib.tsa_mfma_probe.restype = ctypes.c_int
     lib.tsa_mfma_probe.argtypes = [vp, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32), vp]
     lib.tsa_attend_workspace_bytes.restype = sz
@@ -211,9 +211,11 @@ def tsa_compress_v_tiles(desc, V, idx, k_keep, Vt):
     _check(load_library().tsa_compress_v_tiles(ctypes.byref(desc), _ptr(V), _ptr(idx), k_keep, p, n, _stream()))
 
 
-def tsa_attend_fused(desc, Q, K, Vt, idx, inv, k_keep, O=None, Oc=None, block_list=None, block_size=0, max_blocks_per_row=0):
+def tsa_attend_fused(desc, Q, K, Vt, idx, inv, k_keep, O=None, Oc=None, residual=None,
+                     block_list=None, block_size=0, max_blocks_per_row=0):
     _check(load_library().tsa_attend_fused(ctypes.byref(desc), _ptr(Q), _ptr(K), _ptr(Vt), _ptr(idx), _ptr(inv), k_keep,
-                                           _ptr(block_list), block_size, max_blocks_per_row, _ptr(O), _ptr(Oc), _stream()))
+                                           _ptr(block_list), block_size, max_blocks_per_row, _ptr(O), _ptr(Oc),
+                                           _ptr(residual), _stream()))
 
 
 def tsa_forward(desc, Q, K, V, k_keep, O, ws, residual=None, idx_out=None,

@@ -108,7 +108,7 @@ ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
 
 extern "C" {
 
-int tsa_version(void) { return 3; }
+int tsa_version(void) { return 4; }
 
 const char* tsa_last_error(void) { return g_err; }
 
@@ -284,17 +284,17 @@ int tsa_compress_v_tiles(const tsa_desc* desc, const void* V, const int32_t* idx
 int tsa_attend_fused(const tsa_desc* desc, const void* Q, const void* K, const void* Vt,
                      const int32_t* idx, const int32_t* inv, int32_t k_keep,
                      const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
-                     void* O, void* Oc, void* stream) {
+                     void* O, void* Oc, void* residual, void* stream) {
   tsa::Dims dm;
   int rc;
   if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep))) return rc;
   if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(Vt, "Vt")) || (rc = check_ptr(idx, "idx"))) return rc;
-  if (!O && !Oc) return fail(TSA_ERR_ARG, "both O and Oc are NULL");
-  if ((rc = check_ptr(O, "O", true)) || (rc = check_ptr(Oc, "Oc", true))) return rc;
+  if (!O && !Oc && !residual) return fail(TSA_ERR_ARG, "O, Oc and residual are all NULL");
+  if ((rc = check_ptr(O, "O", true)) || (rc = check_ptr(Oc, "Oc", true)) || (rc = check_ptr(residual, "residual", true))) return rc;
   if (O && (rc = check_ptr(inv, "inv"))) return rc;
   if ((rc = check_block_list(block_list, block_size, max_blocks_per_row))) return rc;
   return hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_keep, block_list, max_blocks_per_row, Oc, O,
-                                             (hipStream_t)stream), "tsa_attend_fused");
+                                             residual, (hipStream_t)stream), "tsa_attend_fused");
 }
 
 int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* V, int32_t k_keep,
@@ -325,8 +325,7 @@ int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* 
   // output is materialised only for the residual update.
   if ((rc = hip_status(tsa::launch_compress_tiled(dm, Q, K, V, idx, k_keep, nullptr, nullptr, Vt, st), "tsa_forward(V tiles)"))) return rc;
   if ((rc = hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_keep, block_list, max_blocks_per_row,
-                                                residual ? Oc : nullptr, O, st), "tsa_forward(attend)"))) return rc;
-  if (residual && (rc = hip_status(tsa::launch_residual(dm, Oc, idx, k_keep, residual, st), "tsa_forward(residual)"))) return rc;
+                                                nullptr, O, residual, st), "tsa_forward(attend)"))) return rc;
   if (idx_out) {
     const size_t Hs = (size_t)dm.B * (dm.group_mode ? dm.Hkv : dm.Hq);
     if ((rc = hip_status(hipMemcpyAsync(idx_out, idx, Hs * k_keep * sizeof(int32_t), hipMemcpyDeviceToDevice, st),

@@ -62,11 +62,25 @@ struct AttendArgs {
   // [B,Hq,L,d]: rows of selected tokens are written by the epilogue, all other rows are
   // zero-filled by the workgroup that owns their token range (inv[sel][t] < 0).  O (the compacted
   // output) may be NULL in this form.
+  // X (may be NULL) is the residual stream [B,L,Hq*d]: the epilogue adds output row r, as rounded
+  // to bf16, into X[b, idx[r], h*d .. (h+1)*d) (fp32 add, one rounding); every (token, head) slice
+  // has exactly one writer.
   const int32_t* idx;
   const int32_t* inv;
   __bf16* Of;
+  __bf16* X;
   int L, Hkv;
 };
+
+// two bf16 in one dword: widen to fp32 (exact), add, round each sum to bf16 (nearest even)
+__device__ __forceinline__ uint32_t add_bf16_pairs(uint32_t x, uint32_t o) {
+  const float x0 = __uint_as_float(x << 16), x1 = __uint_as_float(x & 0xffff0000u);
+  const float o0 = __uint_as_float(o << 16), o1 = __uint_as_float(o & 0xffff0000u);
+  bf16x2 s;
+  s[0] = (__bf16)(x0 + o0);
+  s[1] = (__bf16)(x1 + o1);
+  return __builtin_bit_cast(uint32_t, s);
+}
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   bf16x2 v;
@@ -621,7 +635,9 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     if (qrow < a.Lc) {
       __bf16* orow = a.O ? a.O + (bh * a.Lc + qrow) * D : nullptr;
       __bf16* frow = nullptr;                       // fused: the token's row of the full-length output
+      __bf16* xrow = nullptr;                       // fused: the token's slice of the residual stream
       if (FUSED && a.Of) frow = a.Of + (bh * a.L + idx_row[qrow]) * D;
+      if (FUSED && a.X) xrow = a.X + (((long long)b * a.L + idx_row[qrow]) * a.Hq + h) * D;
 #pragma unroll
       for (int dt = 0; dt < ND; ++dt)
 #pragma unroll
@@ -631,6 +647,13 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
           w[1] = pack_bf16(o[qs][dt][4 * q4 + 2] * inv_l, o[qs][dt][4 * q4 + 3] * inv_l);
           if (orow) *(u32x2*)(orow + 32 * dt + 8 * q4 + 4 * hi) = w;
           if (FUSED && frow) *(u32x2*)(frow + 32 * dt + 8 * q4 + 4 * hi) = w;
+          if (FUSED && xrow) {
+            u32x2* px = (u32x2*)(xrow + 32 * dt + 8 * q4 + 4 * hi);
+            u32x2 x = *px;
+            x[0] = add_bf16_pairs(x[0], w[0]);
+            x[1] = add_bf16_pairs(x[1], w[1]);
+            *px = x;
+          }
         }
       if (a.lse && hi == 0) a.lse[bh * a.Lc + qrow] = (m[qs] + log2f(lt)) * kLn2;
     }
@@ -662,20 +685,20 @@ hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale
   a.lse = lse; a.block_list = block_list; a.max_blocks = max_blocks_per_row;
   a.BH = B * Hq; a.Hq = Hq; a.kvh = kv_heads; a.Lc = Lc;
   a.c = scale * kLog2e;
-  a.idx = nullptr; a.inv = nullptr; a.Of = nullptr; a.L = Lc; a.Hkv = kv_heads;
+  a.idx = nullptr; a.inv = nullptr; a.Of = nullptr; a.X = nullptr; a.L = Lc; a.Hkv = kv_heads;
   return launch_any<false>(a, d, st);
 }
 
 hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, const void* Vt, const int32_t* idx,
                                const int32_t* inv, int k_keep, const int32_t* block_list, int max_blocks_per_row,
-                               void* Oc, void* O, hipStream_t st) {
+                               void* Oc, void* O, void* residual, hipStream_t st) {
   AttendArgs a;
   a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
   a.lse = nullptr; a.block_list = block_list; a.max_blocks = max_blocks_per_row;
   a.bl_head_stride = dm.block_list_per_head ? (long long)((k_keep + kBlock - 1) / kBlock) * max_blocks_per_row : 0;
   a.BH = dm.B * dm.Hq; a.Hq = dm.Hq; a.kvh = dm.group_mode ? dm.Hkv : dm.Hq; a.Lc = k_keep;
   a.c = dm.scale * kLog2e;
-  a.idx = idx; a.inv = inv; a.Of = (__bf16*)O; a.L = dm.L; a.Hkv = dm.Hkv;
+  a.idx = idx; a.inv = inv; a.Of = (__bf16*)O; a.X = (__bf16*)residual; a.L = dm.L; a.Hkv = dm.Hkv;
   return launch_any<true>(a, dm.d, st);
 }
 

@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_desc_struct_matches_header(lib):
     assert ctypes.sizeof(tsa.tsa_desc) == 48
-    assert lib.tsa_version() == 3
+    assert lib.tsa_version() == 4
 
 
 def test_keep_count_matches_oracle_rule(lib):

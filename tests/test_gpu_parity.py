@@ -301,17 +301,21 @@ def test_fused_path_equals_the_separate_calls(tsa, B, Hq, Hkv, L, d, k, group_mo
     tsa.tsa_compress(desc, Q, K, V, idx, k, Qc, Kc, Vc)
     tsa.tsa_attend(desc, Qc, Kc, Vc, k, Hs, Oc, tsa.alloc_attend_workspace(desc, k, Hs, gu.DEV), **kw)
     tsa.tsa_decompress(desc, Oc, idx, inv, k, O=O1)
+    x0 = gu.to_dev(gu.rand_bits(r, (B, L, Hq * d)))
+    x1, x2, x3 = x0.clone(), x0.clone(), x0.clone()
+    tsa.tsa_decompress(desc, Oc, idx, inv, k, residual=x1)
     # the two fused launches on the same index sets
     Vt = tsa.alloc_attend_workspace(desc, k, Hs, gu.DEV)
     O2 = torch.full_like(O1, 7.0)
     Oc2 = torch.full_like(Oc, 7.0)
     tsa.tsa_compress_v_tiles(desc, V, idx, k, Vt)
-    tsa.tsa_attend_fused(desc, Q, K, Vt, idx, inv, k, O=O2, Oc=Oc2, **kw)
+    tsa.tsa_attend_fused(desc, Q, K, Vt, idx, inv, k, O=O2, Oc=Oc2, residual=x2, **kw)
     # the whole layer
     O3 = torch.full_like(O1, 9.0)
     idx3 = torch.empty_like(idx)
-    tsa.tsa_forward(desc, Q, K, V, k, O3, ws, idx_out=idx3, **kw)
+    tsa.tsa_forward(desc, Q, K, V, k, O3, ws, idx_out=idx3, residual=x3, **kw)
     torch.cuda.synchronize()
+    assert torch.equal(x2, x1) and torch.equal(x3, x1) and not torch.equal(x1, x0)
     assert torch.equal(idx3, idx)
     assert torch.equal(Oc2, Oc)
     assert torch.equal(O2, O1) and torch.equal(O3, O1)
