@@ -70,8 +70,8 @@ const char* tsa_last_error(void);
 int32_t tsa_keep_count(int32_t L, double tau);
 
 /* Bytes of workspace that tsa_score, tsa_coverage_budget, tsa_select and tsa_forward need for this
- * problem and k_keep (tsa_forward needs the most: scores, index sets, the gathered V and the
- * compacted output; it also covers tsa_attend on the compacted tensors).
+ * problem and k_keep (tsa_forward needs the most: scores, index sets and the gathered V; it also
+ * covers the workspace of tsa_attend on the compacted tensors).
  * Returns 0 if the descriptor or k_keep is invalid. */
 size_t tsa_workspace_bytes(const tsa_desc* desc, int32_t k_keep);
 

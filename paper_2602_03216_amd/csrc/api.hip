@@ -83,13 +83,12 @@ int check_block_list(const int32_t* bl, int32_t block_size, int32_t max_blocks) 
 
 // Carving of the workspace used by tsa_forward (every piece 256-byte aligned).
 struct ForwardWs {
-  size_t scores, score_ws, select_ws, idx, inv, Vt, Oc, total;
+  size_t scores, score_ws, select_ws, idx, inv, Vt, total;
 };
 
 ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
   ForwardWs w;
   const size_t BHq = (size_t)dm.B * dm.Hq, BHkv = (size_t)dm.B * dm.Hkv;
-  const size_t Hs = dm.group_mode ? BHkv : BHq;
   const size_t row = (size_t)dm.d * 2;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off += align256(bytes); return at; };
@@ -99,7 +98,6 @@ ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
   w.idx = take(Hs * k * sizeof(int32_t));
   w.inv = take(Hs * dm.L * sizeof(int32_t));
   w.Vt = take(tsa::v_tiles_bytes(dm.B, dm.group_mode ? dm.Hkv : dm.Hq, k, dm.d));
-  w.Oc = take(BHq * k * row);
   w.total = off > tsa::budget_ws_bytes(dm) ? off : tsa::budget_ws_bytes(dm);
   return w;
 }
@@ -315,7 +313,7 @@ int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* 
   float* scores = (float*)(base + w.scores);
   int32_t* idx = (int32_t*)(base + w.idx);
   int32_t* inv = (int32_t*)(base + w.inv);
-  void* Vt = base + w.Vt; void* Oc = base + w.Oc;
+  void* Vt = base + w.Vt;
   hipStream_t st = (hipStream_t)stream;
   if ((rc = hip_status(tsa::launch_score(dm, Q, K, scores, base + w.score_ws, st), "tsa_forward(score)"))) return rc;
   if ((rc = hip_status(tsa::launch_select(dm, scores, k_keep, idx, inv, base + w.select_ws, st), "tsa_forward(select)"))) return rc;

@@ -13,8 +13,9 @@
 //   O^T = V^T P^T rows = d, cols = queries     -> the P^T operand is exactly what the lane
 //                 already holds (its query, eight keys per MFMA step): no shuffle and no LDS
 //                 round trip for P, and the rescale factor of O is the lane's own.
-// V stays row-major in LDS; the V^T operand comes from ds_read_b64_tr_b16, which hands each
-// lane four keys of one d-column.
+// V arrives as 64-key transposed tiles ([d][64 keys]) and K rows sit in LDS in a permuted order, so
+// that each V^T operand is one 16-byte LDS read holding exactly the eight keys whose probabilities
+// the lane has just packed.
 // The loop is software-pipelined: the QK product of the next half tile is issued together with
 // the softmax arithmetic of the current one, so the matrix pipe and the vector ALU overlap.
 // The O rescale is lazy: the running max is only raised when a row's new max exceeds it by
@@ -486,10 +487,9 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     //    8..15  O^T += V^T(T0, half 0) pA  with  row max of sB          [then the rare raise of m]
     //   16..23  S^T(T1, half 0) -> sA      with  exp(sB) -> pB
     //   24..31  O^T += V^T(T0, half 1) pB  with  row max of sA, staging  [barrier, rare raise of m]
-    // Each chunk consumes one 16-byte LDS fragment per lane (a K fragment, or a V^T fragment from
-    // two transposing reads); fragments are fetched kPF chunks ahead through a small register
-    // ring that runs across the blocks and across iterations, so the LDS latency is hidden even
-    // though the SIMD holds a single wavefront.
+    // Each chunk consumes one 16-byte LDS fragment per lane (a K fragment or a V^T fragment);
+    // fragments are fetched kPF chunks ahead through a small register ring that runs across the
+    // blocks and across iterations, so the LDS latency is hidden.
     constexpr int kPF = TSA_PF, kRing = TSA_RING, kChunks = 4 * NS;
     static_assert(NS == 8 || NS == 4, "chunk stream is laid out for d = 128 or 64");
     constexpr int CPB = kChunks / 4;                       // chunks per block
