@@ -89,7 +89,7 @@ struct ForwardWs {
 ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
   ForwardWs w;
   const size_t BHq = (size_t)dm.B * dm.Hq, BHkv = (size_t)dm.B * dm.Hkv;
-  const size_t row = (size_t)dm.d * 2;
+  const size_t Hs = dm.group_mode ? BHkv : BHq;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off += align256(bytes); return at; };
   w.scores = take(BHq * dm.L * sizeof(float));
