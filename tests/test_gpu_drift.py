@@ -33,3 +33,18 @@ def test_layer_drift(tsa, n_tokens, width, eps):
     # unchanged hidden state: drift exactly zero
     tsa.tsa_layer_drift(a, a, eps, out)
     assert out.item() == 0.0
+
+
+def test_mfma_probe_runs_and_reports_clocks(tsa):
+    """The roofline calibration loop: queues, finishes, and reports a plausible shader clock."""
+    ops = torch.zeros(1 << 15, dtype=torch.bfloat16, device=gu.DEV)
+    blocks = 64
+    sink = torch.empty(blocks * 256, dtype=torch.float32, device=gu.DEV)
+    clocks = torch.zeros(2, dtype=torch.int64, device=gu.DEV)
+    flops, khz = tsa.tsa_mfma_probe(ops, 1000, blocks, sink, clocks)
+    torch.cuda.synchronize()
+    assert flops == blocks * 4 * 1000 * 8 * 2 * 32 * 32 * 16 and khz > 0
+    cyc, ticks = (int(v) for v in clocks.cpu())
+    mhz = cyc / (ticks / (khz * 1e3)) / 1e6
+    assert cyc >= 1000 * 8 * 16 and 500 < mhz < 3500
+    assert not sink.isnan().any() and float(sink.abs().max()) == 0.0      # zero operands: zero accumulators
