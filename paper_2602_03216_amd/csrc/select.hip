@@ -221,6 +221,105 @@ __global__ __launch_bounds__(kThreads) void write_kernel(SelArgs a) {
   }
 }
 
+// Short rows (L <= kSmallL): the whole selection of a row in ONE launch by one workgroup.  The
+// order-preserving keys of the row are kept in LDS (4 bytes per token), the four radix passes, the
+// counting and the stable compaction all run out of LDS; same arithmetic and same result as the
+// sliced kernels above, without six launches whose fixed cost dominates at this size.
+constexpr int kSmallL = 16384;
+
+__global__ __launch_bounds__(kThreads) void select_small_kernel(SelArgs a) {
+  extern __shared__ uint32_t dyn[];
+  uint32_t* keys = dyn;                                   // [L]
+  uint32_t* hist = dyn + a.L;                             // [kWaves][256], then reused
+  __shared__ uint32_t tot[256];
+  __shared__ SelState sh_state;
+  __shared__ uint2 cnt[kWaves];
+  const long long row = blockIdx.x;
+  const float* s = a.scores + row * a.L;
+  int32_t* out_idx = a.idx + row * a.k;
+  int32_t* out_inv = a.inv ? a.inv + row * a.L : nullptr;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  for (int t = tid; t < a.L; t += kThreads) keys[t] = key_at(s, t, a.L, a.ff, a.fl);
+  SelState st;
+  st.prefix = 0u;
+  st.krem = (uint32_t)a.k;
+#pragma unroll 1
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    const uint32_t himask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+    for (int i = tid; i < kWaves * 256; i += kThreads) hist[i] = 0u;
+    __syncthreads();                                      // keys (first pass) and cleared histograms are visible
+    for (int base = 0; base < a.L; base += kThreads) {
+      const int t = base + tid;
+      bool valid = false;
+      uint32_t dg = 0;
+      if (t < a.L) {
+        const uint32_t key = keys[t];
+        valid = (key & himask) == st.prefix;
+        dg = (key >> shift) & 255u;
+      }
+      const unsigned long long act = __ballot(valid);
+      if (act == 0ull) continue;
+      const int leader = __ffsll((long long)act) - 1;
+      const uint32_t dg0 = __shfl(dg, leader);
+      const unsigned long long same = __ballot(valid && dg == dg0);
+      if (same == act) {
+        if (lane == leader) atomicAdd(&hist[wave * 256 + dg0], (uint32_t)__popcll(act));
+      } else if (valid) {
+        atomicAdd(&hist[wave * 256 + dg], 1u);
+      }
+    }
+    __syncthreads();
+    if (tid < 256) {
+      uint32_t c = 0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) c += hist[w * 256 + tid];
+      tot[tid] = c;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      const SelState nx = next_state(tot, st, shift, lane);
+      if (lane == 0) sh_state = nx;
+    }
+    __syncthreads();
+    st = sh_state;
+  }
+  // st.prefix = threshold key T, st.krem = number of keys equal to T to take (in token order)
+  const uint32_t T = st.prefix, need_eq = st.krem;
+  const int seg = ((a.L + kWaves - 1) / kWaves + 63) & ~63;
+  const int t_lo = wave * seg, t_hi = min(a.L, t_lo + seg);
+  uint32_t n_gt = 0, n_eq = 0;
+  for (int base = t_lo; base < t_hi; base += 64) {
+    const int t = base + lane;
+    const bool in = t < t_hi;
+    const uint32_t key = in ? keys[t] : 0u;
+    n_gt += (uint32_t)__popcll(__ballot(in && key > T));
+    n_eq += (uint32_t)__popcll(__ballot(in && key == T));
+  }
+  if (lane == 0) cnt[wave] = make_uint2(n_gt, n_eq);
+  __syncthreads();
+  uint32_t gt_before = 0, eq_before = 0;
+  for (int w = 0; w < wave; ++w) { gt_before += cnt[w].x; eq_before += cnt[w].y; }
+  uint32_t eq_run = eq_before, out_run = gt_before + min(need_eq, eq_before);
+  const unsigned long long lt_mask = (1ull << lane) - 1ull;
+  for (int base = t_lo; base < t_hi; base += 64) {
+    const int t = base + lane;
+    const bool in = t < t_hi;
+    const uint32_t key = in ? keys[t] : 0u;
+    const bool gt = in && key > T;
+    const bool eq = in && key == T;
+    const unsigned long long m_eq = __ballot(eq);
+    const uint32_t eq_rank = eq_run + (uint32_t)__popcll(m_eq & lt_mask);
+    const bool take = gt || (eq && eq_rank < need_eq);
+    const unsigned long long m_take = __ballot(take);
+    const uint32_t pos = out_run + (uint32_t)__popcll(m_take & lt_mask);
+    if (take) out_idx[pos] = t;
+    if (in && out_inv) out_inv[t] = take ? (int32_t)pos : -1;
+    out_run += (uint32_t)__popcll(m_take);
+    eq_run += (uint32_t)__popcll(m_eq);
+  }
+}
+
 // scores [B,Hq,L] -> [B,Hkv,L]: sum of the g heads of each KV group, in head order
 __global__ void group_sum_kernel(const float* __restrict__ s, float* __restrict__ out, int g, int L, long long n) {
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -260,6 +359,17 @@ hipError_t launch_select(const Dims& dm, const float* scores, int k_keep, int32_
   }
   a.idx = idx; a.inv = inv;
   a.L = dm.L; a.k = k_keep; a.ff = dm.force_first; a.fl = dm.force_last; a.nslices = n_slices(dm);
+  if (dm.L <= kSmallL) {
+    const size_t lds = ((size_t)dm.L + kWaves * 256) * sizeof(uint32_t);
+    static bool attr_set = false;
+    if (!attr_set) {
+      const hipError_t e = hipFuncSetAttribute((const void*)select_small_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    select_small_kernel<<<rows, kThreads, lds, st>>>(a);
+    return hipGetLastError();
+  }
   zero_hist_kernel<<<(rows * 1024 + 255) / 256, 256, 0, st>>>(a.rows, rows);
   const dim3 grid(a.nslices, rows);
   hist_kernel<0><<<grid, kThreads, 0, st>>>(a);
