@@ -357,3 +357,61 @@ def test_forward_with_per_head_block_lists(tsa):
     ref = orc.forward(inp.Q, inp.K, inp.V, k, Lq, block_list=bl, block_size=Bs)
     assert np.array_equal(idx.cpu().numpy(), ref["idx"])
     gu.assert_output_close(gu.from_dev(O), ref["O"], "forward(per-head block lists)")
+
+
+def test_random_small_shapes_sweep(tsa):
+    """Thirty seeded random small problems (odd lengths around the 64-key and 256-row tile edges,
+    odd head counts, both head dimensions, batch > 1): attention against the oracle, and the whole
+    layer against the separate calls (bit for bit) on index sets the library selected itself."""
+    r = _rng(31337)
+    for case in range(30):
+        d = int(r.choice([64, 128]))
+        Hkv = int(r.integers(1, 4))
+        g = int(r.integers(1, 4))
+        Hq = Hkv * g
+        B = int(r.integers(1, 3))
+        L = int(r.choice([1, 2, 31, 63, 64, 65, 127, 129, 255, 256, 257, 300, 511, 513, 640, 777]))
+        Lq = int(min(L, r.choice([1, 7, 32, 64, 100])))
+        k = int(r.integers(1, L + 1))
+        group_mode = int(r.integers(0, 2))
+        Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, L, d)), gu.rand_bits(r, (B, Hkv, L, d)), gu.rand_bits(r, (B, Hkv, L, d))
+        tag = "case %d: B=%d Hq=%d Hkv=%d L=%d d=%d Lq=%d k=%d mode=%d" % (case, B, Hq, Hkv, L, d, Lq, k, group_mode)
+        desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq, group_mode=group_mode)
+        Q, K, V = gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb)
+        # dense causal attention of the full sequence against the oracle
+        O = torch.empty((B, Hq, L, d), dtype=torch.bfloat16, device=gu.DEV)
+        tsa.tsa_attend(desc, Q, K, V, L, Hkv, O, tsa.alloc_attend_workspace(desc, L, Hkv, gu.DEV))
+        want = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb))
+        gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), tag)
+        # the layer: fused against separate calls
+        Hs = Hkv if group_mode else Hq
+        ws = _ws(tsa, desc, k)
+        s = torch.empty((B, Hq, L), dtype=torch.float32, device=gu.DEV)
+        idx = torch.empty((B, Hs, k), dtype=torch.int32, device=gu.DEV)
+        inv = torch.empty((B, Hs, L), dtype=torch.int32, device=gu.DEV)
+        Qc = torch.empty((B, Hq, k, d), dtype=torch.bfloat16, device=gu.DEV)
+        Kc = torch.empty((B, Hs, k, d), dtype=torch.bfloat16, device=gu.DEV)
+        Vc, Oc = torch.empty_like(Kc), torch.empty_like(Qc)
+        O1 = torch.full((B, Hq, L, d), 5.0, dtype=torch.bfloat16, device=gu.DEV)
+        O2 = torch.full_like(O1, 7.0)
+        tsa.tsa_score(desc, Q, K, s, ws)
+        tsa.tsa_select(desc, s, k, idx, inv, ws)
+        tsa.tsa_compress(desc, Q, K, V, idx, k, Qc, Kc, Vc)
+        tsa.tsa_attend(desc, Qc, Kc, Vc, k, Hs, Oc, tsa.alloc_attend_workspace(desc, k, Hs, gu.DEV))
+        tsa.tsa_decompress(desc, Oc, idx, inv, k, O=O1)
+        idx2 = torch.empty_like(idx)
+        tsa.tsa_forward(desc, Q, K, V, k, O2, ws, idx_out=idx2)
+        torch.cuda.synchronize()
+        assert torch.equal(idx2, idx) and torch.equal(O2, O1), tag
+        # the selection is a valid top-k of the library's own scores: ascending, k distinct tokens,
+        # nothing left out scores higher than anything kept
+        sel = orc.group_scores(s.cpu().numpy().astype(np.float64), Hq // Hkv) if group_mode else s.cpu().numpy()
+        got = idx.cpu().numpy()
+        for b in range(B):
+            for h in range(Hs):
+                row = got[b, h]
+                assert np.all(np.diff(row) > 0) and row[0] >= 0 and row[-1] < L, tag
+                kept = np.zeros(L, dtype=bool)
+                kept[row] = True
+                if k < L:
+                    assert sel[b, h][kept].min() >= sel[b, h][~kept].max(), tag
