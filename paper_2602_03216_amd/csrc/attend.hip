@@ -316,17 +316,32 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
 
   // ---- fused form: zero rows of the full-length output.  The workgroup owns the tokens from its
   // first selected token up to the next workgroup's first one (the first workgroup of a head starts
-  // at token 0, the last one ends at L) and clears those that are not selected.  Issued first: the
-  // stores drain while the tiles are computed.
-  if (FUSED && a.Of) {
-    constexpr int LPR = D / 8;
-    const int32_t* inv_row = a.inv + bkv * a.L;
+  // at token 0, the last one ends at L) and clears those that inv marks unselected.  The work is
+  // spread over the tile loop, one pass of kThreads / (d/8) rows every z_every iterations (the
+  // look-up in inv for the next pass is in flight meanwhile), so the stores drain under the compute
+  // instead of holding up the start of the workgroup; what is left when the tiles run out is flushed
+  // before the epilogue.
+  constexpr int LPR = D / 8, RPP = kThreads / LPR;
+  const bool zfill = FUSED && a.Of != nullptr;
+  const int32_t* inv_row = nullptr;
+  u32x4* zrow = nullptr;
+  int z_hi = 0, zt = 0, zr = 0;                          // end of the range, next row of this thread, its inv entry
+  int z_every = 1, z_count = 1;
+  if (zfill) {
+    inv_row = a.inv + bkv * a.L;
     const int tok_lo = qt == 0 ? 0 : idx_row[q0];
-    const int tok_hi = q0 + BM >= a.Lc ? a.L : idx_row[q0 + BM];
-    u32x4* orow = (u32x4*)(a.Of + bh * a.L * D) + (tid % LPR);
-    for (int t = tok_lo + tid / LPR; t < tok_hi; t += kThreads / LPR)
-      if (inv_row[t] < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, orow + (long long)t * LPR);
+    z_hi = q0 + BM >= a.Lc ? a.L : idx_row[q0 + BM];
+    zrow = (u32x4*)(a.Of + bh * a.L * D) + (tid % LPR);
+    zt = tok_lo + tid / LPR;
+    zr = zt < z_hi ? inv_row[zt] : 0;
+    const int passes = (z_hi - tok_lo + RPP - 1) / RPP;  // as evenly over the pipelined iterations as they allow
+    z_every = max(1, (q0 / BN - 1) / max(1, passes));
   }
+  auto zero_step = [&]() {
+    if (zr < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)zt * LPR);
+    zt += RPP;
+    zr = zt < z_hi ? inv_row[zt] : 0;
+  };
 
   // Q^T operand fragments (two 32-row sub-tiles) stay in registers for the whole kernel
   bf16x8 qf[QS][NS];
@@ -580,6 +595,10 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
               vreg[i - CH] = __builtin_amdgcn_raw_buffer_load_b128(Vr, gv_off + (i - CH) * kThreads * 16, vload, 0);
             }
           }
+          if (FUSED && blk == 3 && i == (2 * CH < CPB ? 2 * CH : CPB - 1) && zfill && --z_count <= 0) {
+            zero_step();
+            z_count = z_every;
+          }
           if (i == CPB - 1) {
 #pragma unroll
             for (int qs = 0; qs < QS; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32)) * c_;
@@ -624,6 +643,20 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     lds_barrier();
     T0 = T1; T1 = T2; T2 = T3; T3 = T4;
     rotate();
+  }
+
+  // ---- fused form: the zero rows the tile loop did not get to, eight look-ups in flight per thread
+  if (zfill) {
+    constexpr int kBatch = 8;
+    if (zr < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)zt * LPR);
+    for (int t0 = zt + RPP; t0 < z_hi; t0 += kBatch * RPP) {
+      int r[kBatch];
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) r[j] = t0 + j * RPP < z_hi ? inv_row[t0 + j * RPP] : 0;
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j)
+        if (r[j] < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)(t0 + j * RPP) * LPR);
+    }
   }
 
   // ---- epilogue: normalise, round to bf16, store O[query][d] (a lane holds 4 consecutive d per register quad)
