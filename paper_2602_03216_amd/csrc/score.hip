@@ -13,6 +13,13 @@
 // reduction longer than one step.  A workgroup serves one KV head and one chunk of keys for all
 // the query heads of the group: K tiles are staged in LDS once and every wavefront (one query
 // head each) reads its fragments from there.
+// Tiles that every scoring query sees in full (all but the last few of a sequence) take a
+// software-pipelined body: a "unit" is one 32-key x 32-query block (D/16 MFMAs, 16 scores per
+// lane); the MFMAs of the next unit are issued chunk by chunk between the exponentials of the
+// current one, so the matrix pipe and the vector ALU overlap inside the wavefront.  In pass 1 that
+// body does not compute a row max at all: the running max only has to keep the exponentials in
+// range, so the sum itself is the detector (a unit whose sum leaves the range is redone the exact
+// way, with the true max; this happens once per row in practice).
 #include "tsa_internal.h"
 
 namespace tsa {
@@ -21,9 +28,10 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
-constexpr int kMinChunk = 1024;              // keys per workgroup: at least this, a multiple of kTK
+constexpr int kMinChunk = 256;               // keys per workgroup: at least this, a multiple of kTK
 constexpr int kTK = 128;                     // keys per staged K tile
 constexpr float kNegBig = -1.0e30f;
+constexpr float kSumLimit = 1073741824.0f;   // 2^30: a unit's sum of exponentials beyond this means the running max lags too far
 
 constexpr int kMaxQueries = 128;
 
@@ -100,8 +108,123 @@ struct KStage {
   }
 };
 
+
+// ---- pipelined tile bodies (tiles without any mask).  SPT = 32-key sub-tiles of the staged tile
+// that this wavefront owns, starting at `first` (LDS) = its first sub-tile.  Units run in the order
+// (sub-tile, query sub-tile); while unit u is in the vector ALU the MFMAs of unit u + 1 are issued.
+// The K fragments live in ONE set of registers: right after the MFMA that uses fragment i of a
+// sub-tile for the last time, the register is reloaded with fragment i of the next sub-tile, which is
+// consumed a whole unit later.
+
+template <int D, int NQT, int SPT, bool KEYS_ARE_ROWS>
+struct UnitPipe {
+  static constexpr int NS = D / 16, KS = D + 8, U = SPT * NQT;
+  const __bf16* first;
+  int k_rd;
+  bf16x8 kf[NS];
+  __device__ __forceinline__ void load_frag(int sub, int i) { kf[i] = *(const bf16x8*)(&first[32 * sub * KS + k_rd + 16 * i]); }
+  // MFMA i of unit `nu` (compile-time), then the in-place reload if unit nu + 1 starts a new sub-tile
+  __device__ __forceinline__ void step(int nu, int i, const bf16x8 (&qf)[NQT][NS], f32x16& nxt) {
+    if (nu >= U) return;
+    const bf16x8 q = qf[nu % NQT][i];
+    nxt = KEYS_ARE_ROWS ? mfma32(kf[i], q, nxt) : mfma32(q, kf[i], nxt);
+    if (nu + 1 < U && (nu + 1) / NQT != nu / NQT) load_frag((nu + 1) / NQT, i);
+  }
+};
+
+// Pass 1, lane = query: z[qt] += sum over the tile's keys of exp2(x c - m[qt]).
+template <int D, int NQT, int SPT>
+__device__ __forceinline__ void fast_tile_pass1(const __bf16* first, int k_rd, const bf16x8 (&qf)[NQT][D / 16], float c,
+                                                float (&m)[NQT], float (&z)[NQT]) {
+  using Pipe = UnitPipe<D, NQT, SPT, true>;
+  constexpr int NS = Pipe::NS, EPC = 16 / NS, U = Pipe::U;
+  Pipe pp;
+  pp.first = first;
+  pp.k_rd = k_rd;
+#pragma unroll
+  for (int i = 0; i < NS; ++i) pp.load_frag(0, i);
+  f32x16 acc = {0};
+#pragma unroll
+  for (int i = 0; i < NS; ++i) pp.step(0, i, qf, acc);
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int qt = u % NQT;
+    const float mq = m[qt];
+    f32x16 nxt = {0};
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      pp.step(u + 1, i, qf, nxt);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) {
+        const float p = fast_exp2(fmaf(acc[EPC * i + e], c, -mq));
+        if (e & 1) s1 += p; else s0 += p;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    const float sum = s0 + s1;
+    if (sum < kSumLimit) {
+      z[qt] += sum;
+    } else {                                             // out of range (or the very first unit): exact update
+      float mx = acc[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, acc[r]);
+      const float mn = fmaxf(mq, mx * c);
+      float t0 = 0.f, t1 = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        t0 += fast_exp2(fmaf(acc[r], c, -mn));
+        t1 += fast_exp2(fmaf(acc[r + 1], c, -mn));
+      }
+      z[qt] = z[qt] * fast_exp2(mq - mn) + t0 + t1;
+      m[qt] = mn;
+    }
+    acc = nxt;
+  }
+}
+
+// Pass 2, lane = key: s[t] = sum over the queries of exp2(x c - lse[query]); one store per sub-tile.
+template <int D, int NQT, int SPT>
+__device__ __forceinline__ void fast_tile_pass2(const __bf16* first, int k_rd, const bf16x8 (&qf)[NQT][D / 16], float c,
+                                                const float (&lse)[NQT][16], float* out, int hi) {
+  using Pipe = UnitPipe<D, NQT, SPT, false>;
+  constexpr int NS = Pipe::NS, EPC = 16 / NS, U = Pipe::U;
+  Pipe pp;
+  pp.first = first;
+  pp.k_rd = k_rd;
+#pragma unroll
+  for (int i = 0; i < NS; ++i) pp.load_frag(0, i);
+  f32x16 acc = {0};
+#pragma unroll
+  for (int i = 0; i < NS; ++i) pp.step(0, i, qf, acc);
+  float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int qt = u % NQT, sb = u / NQT;
+    f32x16 nxt = {0};
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      pp.step(u + 1, i, qf, nxt);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) {
+        const int r = EPC * i + e;
+        const float p = fast_exp2(fmaf(acc[r], c, -lse[qt][r]));
+        if (e & 1) s1 += p; else s0 += p;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    acc = nxt;
+    if (qt == NQT - 1) {
+      float colsum = s0 + s1;
+      colsum += __shfl_xor(colsum, 32);
+      if (hi == 0) out[32 * sb] = colsum;
+      s0 = s1 = 0.f;
+    }
+  }
+}
+
 template <int D, int NQT>
-__global__ __launch_bounds__(kThreads) void score_pass1(ScoreArgs a) {
+__global__ __launch_bounds__(kThreads, NQT <= 2 ? 2 : 1) void score_pass1(ScoreArgs a) {
   constexpr int QP = 32 * NQT;
   constexpr int KS = D + 8;
   __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kTK * KS];
@@ -128,17 +251,22 @@ __global__ __launch_bounds__(kThreads) void score_pass1(ScoreArgs a) {
     const bool act = hh < g;
     const long long bh = b * a.Hq + kv * g + (act ? hh : 0);
     bf16x8 qf[NQT][D / 16];
+    stg.load(c_begin);                                 // first K tile and the Q fragments are in flight together
     load_q_frags<D, NQT>(a, bh, lo, hi, qf);
     float m[NQT], z[NQT];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) { m[qt] = kNegBig; z[qt] = 0.f; }
-    stg.load(c_begin);
     stg.store(Ks[0]);
     int par = 0;
     for (int k0 = c_begin; k0 < c_end; k0 += kTK) {
       __syncthreads();                                 // tile k0 is staged, the other buffer is free
       if (k0 + kTK < c_end) stg.load(k0 + kTK);        // in flight during the math below
-      if (act) {
+      if (act && k0 + kTK - 1 <= a.min_pos && k0 + kTK <= a.L) {   // every query sees the whole tile
+        const __bf16* first = &Ks[par][32 * role.kpart * sub_per_tile * KS];
+        if (sub_per_tile == 4) fast_tile_pass1<D, NQT, 4>(first, k_rd, qf, a.c, m, z);
+        else if (sub_per_tile == 2) fast_tile_pass1<D, NQT, 2>(first, k_rd, qf, a.c, m, z);
+        else fast_tile_pass1<D, NQT, 1>(first, k_rd, qf, a.c, m, z);
+      } else if (act) {
         for (int sb = 0; sb < sub_per_tile; ++sb) {
           const int sub = role.kpart * sub_per_tile + sb;
           const int t0 = k0 + 32 * sub;
@@ -231,7 +359,7 @@ __global__ __launch_bounds__(256) void score_lse(ScoreArgs a, int QP, long long 
 }
 
 template <int D, int NQT>
-__global__ __launch_bounds__(kThreads) void score_pass2(ScoreArgs a) {
+__global__ __launch_bounds__(kThreads, NQT <= 2 ? 2 : 1) void score_pass2(ScoreArgs a) {
   constexpr int QP = 32 * NQT;
   constexpr int KS = D + 8;
   __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kTK * KS];
@@ -253,6 +381,8 @@ __global__ __launch_bounds__(kThreads) void score_pass2(ScoreArgs a) {
     const int hh = r0 + role.hslot;
     const bool act = hh < g;
     const long long bh = b * a.Hq + kv * g + (act ? hh : 0);
+    __syncthreads();                                   // previous round is done with both buffers
+    stg.load(c_begin);                                 // first K tile, Q fragments and lse are in flight together
     bf16x8 qf[NQT][D / 16];
     load_q_frags<D, NQT>(a, bh, lo, hi, qf);
     // log2-sum-exp of the queries this lane sees as accumulator rows
@@ -261,14 +391,19 @@ __global__ __launch_bounds__(kThreads) void score_pass2(ScoreArgs a) {
     for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) lse[qt][r] = a.lse2[bh * QP + 32 * qt + c_row(r, hi)];
-    __syncthreads();                                   // previous round is done with both buffers
-    stg.load(c_begin);
     stg.store(Ks[0]);
     int par = 0;
     for (int k0 = c_begin; k0 < c_end; k0 += kTK) {
       __syncthreads();
       if (k0 + kTK < c_end) stg.load(k0 + kTK);
-      if (act) {
+      if (act && k0 + kTK - 1 <= a.min_pos && k0 + kTK <= a.L) {   // no query is hidden from any key of the tile
+        const int sub0 = role.kpart * sub_per_tile;
+        const __bf16* first = &Ks[par][32 * sub0 * KS];
+        float* out = a.scores + bh * a.L + k0 + 32 * sub0 + lo;
+        if (sub_per_tile == 4) fast_tile_pass2<D, NQT, 4>(first, k_rd, qf, a.c, lse, out, hi);
+        else if (sub_per_tile == 2) fast_tile_pass2<D, NQT, 2>(first, k_rd, qf, a.c, lse, out, hi);
+        else fast_tile_pass2<D, NQT, 1>(first, k_rd, qf, a.c, lse, out, hi);
+      } else if (act) {
         for (int sb = 0; sb < sub_per_tile; ++sb) {
           const int sub = role.kpart * sub_per_tile + sb;
           const int t0 = k0 + 32 * sub;
@@ -340,10 +475,11 @@ hipError_t run(const ScoreArgs& a, int BH, hipStream_t st) {
 }
 
 // Keys per workgroup: long enough that the start-up of a workgroup (Q fragments, first K tile)
-// is amortised, short enough for about four workgroups per CU.
+// is amortised, short enough for two workgroups per CU (as many as the LDS tiles allow to be
+// resident, so the launch runs as a single round).
 inline int chunk_for(const Dims& dm) {
   const long long total = (long long)dm.L * dm.B * dm.Hkv;
-  long long c = total / (256 * 4);
+  long long c = total / (256 * 2);
   c = (c + kTK - 1) / kTK * kTK;
   if (c < kMinChunk) c = kMinChunk;
   if (c > 8192) c = 8192;
