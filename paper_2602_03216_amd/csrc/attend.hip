@@ -119,6 +119,7 @@ struct TileGen {
   const int32_t* la;
   const int32_t* lb;
   int ca, cb, ia, ib, sub, kb, use;
+  int a_cur, b_cur;            // next unread entry of each list (INT_MAX: exhausted)
   int plain_n, plain_i;
   bool plain;
   __device__ Tile next() {
@@ -129,12 +130,14 @@ struct TileGen {
       return t;
     }
     if (sub == 0) {
-      const int a = ia < ca ? la[ia] : INT_MAX, b = ib < cb ? lb[ib] : INT_MAX;
+      // a_cur / b_cur were read from the lists when the previous block was handed out, two tiles
+      // ago: the look-up is never waited for
+      const int a = a_cur, b = b_cur;
       kb = min(a, b);
       if (kb == INT_MAX) return Tile{-1, 0};
       use = (a == kb ? 1 : 0) | (b == kb ? 2 : 0);
-      ia += (a == kb);
-      ib += (b == kb);
+      if (a == kb) { ++ia; a_cur = ia < ca ? la[ia] : INT_MAX; }
+      if (b == kb) { ++ib; b_cur = ib < cb ? lb[ib] : INT_MAX; }
       sub = 1;
       return Tile{kb * kBlock, use};
     }
@@ -326,7 +329,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const int32_t* inv_row = nullptr;
   u32x4* zrow = nullptr;
   int z_hi = 0, zt = 0, zr = 0;                          // end of the range, next row of this thread, its inv entry
-  int z_every = 1, z_count = 1;
+  int z_every = 1, z_count = 1, z_passes = 1;
   if (zfill) {
     inv_row = a.inv + bkv * a.L;
     const int tok_lo = qt == 0 ? 0 : idx_row[q0];
@@ -334,8 +337,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     zrow = (u32x4*)(a.Of + bh * a.L * D) + (tid % LPR);
     zt = tok_lo + tid / LPR;
     zr = zt < z_hi ? inv_row[zt] : 0;
-    const int passes = (z_hi - tok_lo + RPP - 1) / RPP;  // as evenly over the pipelined iterations as they allow
-    z_every = max(1, (q0 / BN - 1) / max(1, passes));
+    z_passes = (z_hi - tok_lo + RPP - 1) / RPP;
   }
   auto zero_step = [&]() {
     if (zr < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)zt * LPR);
@@ -368,6 +370,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   gen.plain_i = 0;
   gen.plain_n = (min(q0 + BM, a.Lc) + BN - 1) / BN;
   gen.ia = gen.ib = gen.sub = gen.kb = gen.use = gen.ca = gen.cb = 0;
+  gen.a_cur = gen.b_cur = INT_MAX;
   gen.la = gen.lb = nullptr;
   if (!gen.plain) {
     const int nqb = (a.Lc + kBlock - 1) / kBlock;
@@ -379,6 +382,14 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
       gen.lb = bl + (long long)qb * a.max_blocks;
       gen.cb = count_valid(gen.lb, a.max_blocks, qb);
     }
+    if (gen.ca > 0) gen.a_cur = gen.la[0];
+    if (gen.cb > 0) gen.b_cur = gen.lb[0];
+  }
+
+  // zero rows: as evenly over the pipelined iterations as their number allows
+  if (zfill) {
+    const int n_pipelined = gen.plain ? q0 / BN - 1 : 2 * max(gen.ca, gen.cb) - 6;
+    z_every = max(1, n_pipelined / max(1, z_passes));
   }
 
   // ---- staging: global -> registers -> LDS in 16-byte chunks.  A K tile is 64 rows of the
@@ -491,135 +502,143 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   //   QK(T1, half 0)      with  exp(sB)
   //   PV(T0, half 1)      with  max(sA of T1), staging  [then the rare raise of m]
 
-  // ---- plain causal mode: tiles that lie entirely below the workgroup's first row need no mask
-  // and no per-wavefront decisions; loads past the end return zeros, so nothing in this loop is
-  // conditional except the rare raise of the running max.
-  if (gen.plain) {
-    const int n_fast = q0 / BN - 1;                      // T0 and T1 both below the diagonal
-    int t = 0;
-    // The iteration is a stream of 32 chunks of two MFMAs each:
-    //    0.. 7  S^T(T0, half 1) -> sB      with  exp(sA) -> pA
-    //    8..15  O^T += V^T(T0, half 0) pA  with  row max of sB          [then the rare raise of m]
-    //   16..23  S^T(T1, half 0) -> sA      with  exp(sB) -> pB
-    //   24..31  O^T += V^T(T0, half 1) pB  with  row max of sA, staging  [barrier, rare raise of m]
-    // Each chunk consumes one 16-byte LDS fragment per lane (a K fragment or a V^T fragment);
-    // fragments are fetched kPF chunks ahead through a small register ring that runs across the
-    // blocks and across iterations, so the LDS latency is hidden.
-    constexpr int kPF = TSA_PF, kRing = TSA_RING, kChunks = 4 * NS;
-    static_assert(NS == 8 || NS == 4, "chunk stream is laid out for d = 128 or 64");
-    constexpr int CPB = kChunks / 4;                       // chunks per block
-    // slot = chunk % kRing must mean the same slot in consecutive iterations; a fragment must not be
-    // overwritten before it is consumed; and the fragments fetched across the iteration boundary
-    // must all belong to block 0 (K of the next tile, complete since the previous barrier), not to
-    // the V tile that this iteration is still writing
-    static_assert(kChunks % kRing == 0 && kRing > kPF && kPF <= CPB, "fragment ring does not fit the chunk stream");
-    bf16x8 kfr[kRing];
-    // fragment fetch for chunk c of the iteration whose tiles sit in (kc_, kn_, vc_)
-    auto fetch = [&](int c, const __bf16* kc_, const __bf16* kn_, const __bf16* vc_) {
-      const int blk = c / CPB, i = c % CPB, slot = c % kRing;
-      if (blk == 0) kfr[slot] = *(const bf16x8*)(&kc_[32 * KS + k_rd + 16 * i]);
-      else if (blk == 2) kfr[slot] = *(const bf16x8*)(&kn_[k_rd + 16 * i]);
-      else {
-        const int hf = i / ND, dt = i % ND;
-        kfr[slot] = *(const bf16x8*)(&vc_[v_rd + (32 * dt) * VS + (blk == 3 ? 32 : 0) + 16 * hf]);
-      }
-    };
-    if (n_fast > 0) {
-#pragma unroll
-      for (int c = 0; c < kPF; ++c) fetch(c, kc, kn, vc);
+  // ---- the pipelined iteration: one key tile that lies entirely below the workgroup's first
+  // row and is used by all its wavefronts (as is the tile after it) needs no mask and no
+  // per-wavefront decisions; loads past the end return zeros, so nothing in it is conditional
+  // except the rare raise of the running max.
+  // The iteration is a stream of 32 chunks of two MFMAs each:
+  //    0.. 7  S^T(T0, half 1) -> sB      with  exp(sA) -> pA
+  //    8..15  O^T += V^T(T0, half 0) pA  with  row max of sB          [then the rare raise of m]
+  //   16..23  S^T(T1, half 0) -> sA      with  exp(sB) -> pB
+  //   24..31  O^T += V^T(T0, half 1) pB  with  row max of sA, staging  [barrier, rare raise of m]
+  // Each chunk consumes one 16-byte LDS fragment per lane (a K fragment or a V^T fragment);
+  // fragments are fetched kPF chunks ahead through a small register ring that runs across the
+  // blocks and across iterations, so the LDS latency is hidden.
+  constexpr int kPF = TSA_PF, kRing = TSA_RING, kChunks = 4 * NS;
+  static_assert(NS == 8 || NS == 4, "chunk stream is laid out for d = 128 or 64");
+  constexpr int CPB = kChunks / 4;                       // chunks per block
+  // slot = chunk % kRing must mean the same slot in consecutive iterations; a fragment must not be
+  // overwritten before it is consumed; and the fragments fetched across the iteration boundary
+  // must all belong to block 0 (K of the next tile, complete since the previous barrier), not to
+  // the V tile that this iteration is still writing
+  static_assert(kChunks % kRing == 0 && kRing > kPF && kPF <= CPB, "fragment ring does not fit the chunk stream");
+  bf16x8 kfr[kRing];
+  // fragment fetch for chunk c of the iteration whose tiles sit in (kc_, kn_, vc_)
+  auto fetch = [&](int c, const __bf16* kc_, const __bf16* kn_, const __bf16* vc_) {
+    const int blk = c / CPB, i = c % CPB, slot = c % kRing;
+    if (blk == 0) kfr[slot] = *(const bf16x8*)(&kc_[32 * KS + k_rd + 16 * i]);
+    else if (blk == 2) kfr[slot] = *(const bf16x8*)(&kn_[k_rd + 16 * i]);
+    else {
+      const int hf = i / ND, dt = i % ND;
+      kfr[slot] = *(const bf16x8*)(&vc_[v_rd + (32 * dt) * VS + (blk == 3 ? 32 : 0) + 16 * hf]);
     }
-    for (; t < n_fast; ++t) {
-      float mxc[QS], mx[QS], ps0[QS], ps1[QS];
-      f32x16 acc[QS];
-      const int vload = (t + 2) * BN * ROWB, tokload = (t + 4) * BN;
+  };
+  auto prime_ring = [&]() {
 #pragma unroll
-      for (int c = 0; c < kChunks; ++c) {
-        const int blk = c / CPB, i = c % CPB, slot = c % kRing;
-        // prefetch kPF chunks ahead; the first chunks of the next iteration read the rotated slots
-        if (c + kPF < kChunks) fetch(c + kPF, kc, kn, vc);
-        else fetch(c + kPF - kChunks, kn, kf, vn);
-        if (blk == 0 || blk == 2) {
-          const f32x16 (&s_in)[QS] = blk == 0 ? sA : sB;
-          uint32_t (&p_out)[QS][8] = blk == 0 ? pA : pB;
-          constexpr int EPS = 16 / NS;
-          // one MFMA, then the exponentials of one query sub-tile: the vector work runs in the
-          // shadow of the MFMA that was just issued
+    for (int c = 0; c < kPF; ++c) fetch(c, kc, kn, vc);
+  };
+  // vload: byte offset of the V tile to prefetch (tile T2), tokload: first compacted row of the
+  // K tile whose rows are looked up (tile T4)
+  auto fast_iter = [&](const int vload, const int tokload) {
+    float mxc[QS], mx[QS], ps0[QS], ps1[QS];
+    f32x16 acc[QS];
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) {
+      const int blk = c / CPB, i = c % CPB, slot = c % kRing;
+      // prefetch kPF chunks ahead; the first chunks of the next iteration read the rotated slots
+      if (c + kPF < kChunks) fetch(c + kPF, kc, kn, vc);
+      else fetch(c + kPF - kChunks, kn, kf, vn);
+      if (blk == 0 || blk == 2) {
+        const f32x16 (&s_in)[QS] = blk == 0 ? sA : sB;
+        uint32_t (&p_out)[QS][8] = blk == 0 ? pA : pB;
+        constexpr int EPS = 16 / NS;
+        // one MFMA, then the exponentials of one query sub-tile: the vector work runs in the
+        // shadow of the MFMA that was just issued
+#pragma unroll
+        for (int qs = 0; qs < QS; ++qs) {
+          if (i == 0) { acc[qs] = f32x16{0}; ps0[qs] = ps1[qs] = 0.f; }
+          acc[qs] = mfma32(kfr[slot], qf[qs][i], acc[qs]);
+#pragma unroll
+          for (int e = 0; e < EPS; e += 2) {
+            const int r = EPS * i + e;
+            const float p0 = fast_exp2(fmaf(s_in[qs][r], c_, -m[qs]));
+            const float p1 = fast_exp2(fmaf(s_in[qs][r + 1], c_, -m[qs]));
+            ps0[qs] += p0;
+            ps1[qs] += p1;
+            p_out[qs][r >> 1] = pack_bf16(p0, p1);
+          }
+          if (qs + 1 < QS) __builtin_amdgcn_sched_barrier(0);
+        }
+        if (i == CPB - 1) {
+          f32x16 (&s_out)[QS] = blk == 0 ? sB : sA;
 #pragma unroll
           for (int qs = 0; qs < QS; ++qs) {
-            if (i == 0) { acc[qs] = f32x16{0}; ps0[qs] = ps1[qs] = 0.f; }
-            acc[qs] = mfma32(kfr[slot], qf[qs][i], acc[qs]);
-#pragma unroll
-            for (int e = 0; e < EPS; e += 2) {
-              const int r = EPS * i + e;
-              const float p0 = fast_exp2(fmaf(s_in[qs][r], c_, -m[qs]));
-              const float p1 = fast_exp2(fmaf(s_in[qs][r + 1], c_, -m[qs]));
-              ps0[qs] += p0;
-              ps1[qs] += p1;
-              p_out[qs][r >> 1] = pack_bf16(p0, p1);
-            }
-            if (qs + 1 < QS) __builtin_amdgcn_sched_barrier(0);
-          }
-          if (i == CPB - 1) {
-            f32x16 (&s_out)[QS] = blk == 0 ? sB : sA;
-#pragma unroll
-            for (int qs = 0; qs < QS; ++qs) {
-              s_out[qs] = acc[qs];
-              l[qs] += ps0[qs] + ps1[qs];
-            }
-          }
-        } else {
-          const f32x16 (&s_in)[QS] = blk == 1 ? sB : sA;
-          const uint32_t (&pb)[QS][8] = blk == 1 ? pA : pB;
-          const int hf = i / ND, dt = i % ND;
-          constexpr int EPC = 16 / CPB;
-          const bf16x8 vf = kfr[slot];
-#pragma unroll
-          for (int qs = 0; qs < QS; ++qs) {
-            if (i == 0) mx[qs] = s_in[qs][0];
-            o[qs][dt] = mfma32(vf, p_operand(pb[qs], hf), o[qs][dt]);
-            if (EPC == 2) mx[qs] = __builtin_fmaxf(__builtin_fmaxf(mx[qs], s_in[qs][2 * i]), s_in[qs][2 * i + 1]);
-            else {
-#pragma unroll
-              for (int e = 0; e < EPC; ++e) mx[qs] = fmaxf(mx[qs], s_in[qs][EPC * i + e]);
-            }
-            if (qs + 1 < QS) __builtin_amdgcn_sched_barrier(0);
-          }
-          if (blk == 3) {                 // K(t+2) -> kf, V(t+1) -> vn, then refill the registers
-            if (i < CH) {
-              *(u32x4*)(&kf[lk_off + i * kRowsPerPass * KS]) = kreg[i];
-              kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, ktok[i] * ROWB + 16 * st_col, 0, 0);
-              if (FUSED) ktok[i] = __builtin_amdgcn_raw_buffer_load_b32(Ir, (st_row + i * kRowsPerPass) * 4, tokload * 4, 0);
-              else ktok[i] = tokload + st_row + i * kRowsPerPass;
-            } else if (i < 2 * CH) {
-              *(u32x4*)(&vn[lv_off + (i - CH) * kVRowsPerPass * VS]) = vreg[i - CH];
-              vreg[i - CH] = __builtin_amdgcn_raw_buffer_load_b128(Vr, gv_off + (i - CH) * kThreads * 16, vload, 0);
-            }
-          }
-          if (FUSED && blk == 3 && i == (2 * CH < CPB ? 2 * CH : CPB - 1) && zfill && --z_count <= 0) {
-            zero_step();
-            z_count = z_every;
-          }
-          if (i == CPB - 1) {
-#pragma unroll
-            for (int qs = 0; qs < QS; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32)) * c_;
+            s_out[qs] = acc[qs];
+            l[qs] += ps0[qs] + ps1[qs];
           }
         }
-        __builtin_amdgcn_sched_barrier(0);
-        if (c == 2 * CPB - 1) raise_max<ND, QS>(mxc, m, l, o);
+      } else {
+        const f32x16 (&s_in)[QS] = blk == 1 ? sB : sA;
+        const uint32_t (&pb)[QS][8] = blk == 1 ? pA : pB;
+        const int hf = i / ND, dt = i % ND;
+        constexpr int EPC = 16 / CPB;
+        const bf16x8 vf = kfr[slot];
+#pragma unroll
+        for (int qs = 0; qs < QS; ++qs) {
+          if (i == 0) mx[qs] = s_in[qs][0];
+          o[qs][dt] = mfma32(vf, p_operand(pb[qs], hf), o[qs][dt]);
+          if (EPC == 2) mx[qs] = __builtin_fmaxf(__builtin_fmaxf(mx[qs], s_in[qs][2 * i]), s_in[qs][2 * i + 1]);
+          else {
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) mx[qs] = fmaxf(mx[qs], s_in[qs][EPC * i + e]);
+          }
+          if (qs + 1 < QS) __builtin_amdgcn_sched_barrier(0);
+        }
+        if (blk == 3) {                 // K(t+2) -> kf, V(t+1) -> vn, then refill the registers
+          if (i < CH) {
+            *(u32x4*)(&kf[lk_off + i * kRowsPerPass * KS]) = kreg[i];
+            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, ktok[i] * ROWB + 16 * st_col, 0, 0);
+            if (FUSED) ktok[i] = __builtin_amdgcn_raw_buffer_load_b32(Ir, (st_row + i * kRowsPerPass) * 4, tokload * 4, 0);
+            else ktok[i] = tokload + st_row + i * kRowsPerPass;
+          } else if (i < 2 * CH) {
+            *(u32x4*)(&vn[lv_off + (i - CH) * kVRowsPerPass * VS]) = vreg[i - CH];
+            vreg[i - CH] = __builtin_amdgcn_raw_buffer_load_b128(Vr, gv_off + (i - CH) * kThreads * 16, vload, 0);
+          }
+        }
+        if (FUSED && blk == 3 && i == (2 * CH < CPB ? 2 * CH : CPB - 1) && zfill && --z_count <= 0) {
+          zero_step();
+          z_count = z_every;
+        }
+        if (i == CPB - 1) {
+#pragma unroll
+          for (int qs = 0; qs < QS; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32)) * c_;
+        }
       }
-      lds_barrier();
-      raise_max<ND, QS>(mxc, m, l, o);
-      rotate();
+      __builtin_amdgcn_sched_barrier(0);
+      if (c == 2 * CPB - 1) raise_max<ND, QS>(mxc, m, l, o);
     }
-    if (t > 0) {                                           // hand over to the general loop
-      auto tile_at = [&](int i) { return i < gen.plain_n ? Tile{i * BN, 3} : Tile{-1, 0}; };
-      T0 = tile_at(t); T1 = tile_at(t + 1); T2 = tile_at(t + 2); T3 = tile_at(t + 3);
-      gen.plain_i = t + 4;
-    }
-  }
+    lds_barrier();
+    raise_max<ND, QS>(mxc, m, l, o);
+    rotate();
+    };
 
-  // ---- general loop: diagonal tiles (mask, wavefronts that have nothing to do) and block lists
+  // ---- tile loop.  A tile takes the pipelined iteration when it and the tile after it lie below
+  // the workgroup's first row and are used by both halves of the workgroup (plain causal: every
+  // tile but the last five; sink + window lists: all but the first and last few); diagonal tiles,
+  // tiles only one half visits and the tile in front of either take the general iteration, with
+  // masks and per-wavefront decisions.  Both keep the same invariant, so they alternate freely.
+  auto pipelined = [&](const Tile& t) -> bool { return t.k0 >= 0 && t.use == 3 && t.k0 + BN <= q0; };
   while (T0.k0 >= 0) {
+    if (pipelined(T0) && pipelined(T1)) {
+      prime_ring();
+      do {
+        const Tile T4 = gen.next();
+        // tiles that do not exist are replaced by tile 0 in the prefetches: loaded, never used
+        fast_iter(max(T2.k0, 0) * ROWB, max(T4.k0, 0));
+        T0 = T1; T1 = T2; T2 = T3; T3 = T4;
+      } while (pipelined(T0) && pipelined(T1));
+      if (T0.k0 < 0) break;
+    }
     qk_half<D, QS>(kc + 32 * KS, k_rd, qf, sB);
     if (wave_active(T0)) {
       if (T0.k0 + BN - 1 > wrow0) mask_half<QS>(sB, T0.k0 + 32, hi, wrow0 + lo);
