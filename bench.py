@@ -147,6 +147,50 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
     return out, inp
 
 
+def bench_stack(tsa, torch, gen, steps, warmup):
+    """One layer of the interleaved stack workload (64K tokens, 28 query / 4 KV heads): tsa_forward
+    composed with the sink + sliding-window block list in compacted index space, output added into
+    the residual stream; next to the same layer without the block list and to own dense attention."""
+    import numpy as np
+    inp = gen.make_inputs(5, layer=0)
+    cfg = inp.cfg
+    dev = "cuda:0"
+    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    Q, K, V = to_dev(inp.Q), to_dev(inp.K), to_dev(inp.V)
+    B, Hq, Hkv, L, d, Lq = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"]
+    tau = cfg["taus"][0]
+    k = tsa.tsa_keep_count(L, tau)
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq)
+    O = torch.empty((B, Hq, L, d), dtype=torch.bfloat16, device=dev)
+    x = to_dev(gen.make_residual(cfg, gen.SEED_BASE + 5000))
+    bl_np = gen.sink_window_block_list(k, cfg["block_size"], cfg["window"], 1)
+    bl = torch.from_numpy(bl_np).to(dev)
+    ws = tsa.alloc_workspace(desc, k, dev)
+    masked = lambda: tsa.tsa_forward(desc, Q, K, V, k, O, ws, residual=x, block_list=bl,
+                                     block_size=cfg["block_size"], max_blocks_per_row=bl_np.shape[1])
+    plain = lambda: tsa.tsa_forward(desc, Q, K, V, k, O, ws, residual=x)
+    ws_dense = tsa.alloc_attend_workspace(desc, L, Hkv, dev)
+    dense = lambda: tsa.tsa_attend(desc, Q, K, V, L, Hkv, O, ws_dense)
+    t = {}
+    for name, fn, it in (("masked", masked, steps), ("plain", plain, steps), ("dense", dense, 3)):
+        for _ in range(warmup if name != "dense" else 1):
+            fn()
+        torch.cuda.synchronize()
+        t[name] = _events_ms(fn, it, torch)
+    # flops of the masked attention: every listed (query block, key block) pair, the diagonal one causal
+    bs = cfg["block_size"]
+    n_pairs = int((bl_np >= 0).sum())
+    nb = bl_np.shape[0]
+    masked_flops = 4 * Hq * d * ((n_pairs - nb) * bs * bs + nb * bs * (bs + 1) // 2)
+    return {"workload": cfg["name"], "L": L, "Hq": Hq, "Hkv": Hkv, "d": d, "tau": tau, "k_keep": k, "layers": cfg["layers"],
+            "block_size": bs, "window": cfg["window"],
+            "forward_masked_residual_ms_per_layer": t["masked"], "forward_plain_residual_ms_per_layer": t["plain"],
+            "dense_ms": t["dense"], "speedup_layer_vs_dense_masked": t["dense"] / t["masked"],
+            "speedup_layer_vs_dense_plain": t["dense"] / t["plain"],
+            "masked_attend_algorithmic_tflop": masked_flops / 1e12,
+            "dense_tflops": algorithmic_work(cfg, L)["dense_flops"] / t["dense"] / 1e9}
+
+
 def cpu_baseline(inp, k, budget_rows=4096):
     """The CPU oracle, as it stands, on a bounded sample of the headline workload: scoring and
     selection in full; compression, attention and decompression for a few heads / rows, scaled
@@ -263,6 +307,7 @@ def main():
     if not args.quick:
         r32, _ = bench_workload(tsa, torch, gen, 3, gen.CONFIGS[3]["taus"], args.steps, args.warmup, dense_iters=5, part_iters=10)
         detail["gqa_32k"] = r32
+        detail["stack_64k"] = bench_stack(tsa, torch, gen, args.steps, args.warmup)
     head = r128["per_tau"][str(head_tau)]
     cfg = inp128.cfg
     import numpy as np

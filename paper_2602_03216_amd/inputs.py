@@ -217,6 +217,22 @@ def make_residual(cfg: dict, seed: int) -> np.ndarray:
     return f32_to_bf16_bits(x)
 
 
+def sink_window_block_list(Lc: int, block_size: int, window: int, n_sink_blocks: int = 1) -> np.ndarray:
+    """Block list of the stack workload's mask in compacted index space (sink + sliding window):
+    query block qb lists the first n_sink_blocks key blocks and the blocks qb - window/block_size .. qb.
+    Returns [ceil(Lc / block_size), n_sink_blocks + window/block_size + 1] int32, rows ascending
+    without duplicates, padded with -1."""
+    nb = (Lc + block_size - 1) // block_size
+    wb = window // block_size
+    width = min(nb, n_sink_blocks + wb + 1)
+    out = np.full((nb, width), -1, dtype=np.int32)
+    for qb in range(nb):
+        first = max(0, qb - wb)
+        row = list(range(min(n_sink_blocks, first))) + list(range(first, qb + 1))
+        out[qb, :len(row)] = row
+    return out
+
+
 def vertical_slash_block_lists(B: int, Hq: int, n_blocks: int, seed: int, n_vertical: int = 3, slash_blocks: int = 2,
                                n_extra: int = 2) -> np.ndarray:
     """Per-head block lists of the "vertical + slash" kind block-sparse prefill methods produce, in

@@ -41,3 +41,20 @@ def test_reduced_gqa_recipe_with_sinks():
     assert np.all(idx[0, :, :4] == np.arange(4))          # the four sink tokens are kept by every head
     rec = np.mean([np.isin(inp.planted[h], idx[0, h]).mean() for h in range(32)])
     assert rec > 0.9
+
+
+def test_sink_window_block_list_matches_the_pair_predicate():
+    """The generator's block list lists key block kb for query block qb exactly when kb <= qb and
+    (kb is a sink block or qb - kb <= window / block): checked pair by pair, and against the
+    list the oracle builds for its own attention."""
+    for Lc, bs, win, ns in ((1000, 128, 256, 1), (4096, 128, 4096, 1), (777, 64, 128, 2), (130, 128, 512, 1)):
+        bl = gen.sink_window_block_list(Lc, bs, win, ns)
+        nb = (Lc + bs - 1) // bs
+        assert bl.shape[0] == nb
+        for qb in range(nb):
+            row = [int(v) for v in bl[qb] if v >= 0]
+            assert row == sorted(set(row))
+            want = [kb for kb in range(nb) if kb <= qb and (kb < ns or qb - kb <= win // bs)]
+            assert row == want
+        ref = orc.lambda_block_list(Lc, bs, win, ns)
+        assert all([v for v in a if v >= 0] == [v for v in b if v >= 0] for a, b in zip(bl.tolist(), ref.tolist()))
