@@ -222,7 +222,9 @@ def test_attend_large_logits_and_scale(tsa):
     gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(large logits)")
 
 
-@pytest.mark.parametrize("Lc,window", [(1000, 256), (1300, 128), (640, 4096)])
+# (3000, 1024): long stretches of pipelined iterations between the sink block, the window's first
+# block (visited by half of the workgroup only) and the diagonal
+@pytest.mark.parametrize("Lc,window", [(1000, 256), (1300, 128), (640, 4096), (3000, 1024)])
 def test_attend_block_list(tsa, Lc, window):
     r = _rng(500 + Lc)
     B, Hq, Hk, d, Bs = 1, 4, 2, 128, 128
@@ -321,7 +323,7 @@ def test_fused_path_equals_the_separate_calls(tsa, B, Hq, Hkv, L, d, k, group_mo
     assert torch.equal(O2, O1) and torch.equal(O3, O1)
 
 
-@pytest.mark.parametrize("Hq,Hk,Lc,d", [(4, 2, 1000, 128), (3, 3, 1500, 64)])
+@pytest.mark.parametrize("Hq,Hk,Lc,d", [(4, 2, 1000, 128), (3, 3, 1500, 64), (2, 1, 2600, 128)])
 def test_attend_per_head_block_lists(tsa, Hq, Hk, Lc, d):
     """Block-sparse composition with a different pattern for every head (vertical + slash)."""
     from paper_2602_03216_amd import inputs as gen
