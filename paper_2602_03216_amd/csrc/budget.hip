@@ -19,7 +19,7 @@ namespace {
 
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
-constexpr int kSlice = 16384;
+constexpr int kSlice = 2048;      // tokens per workgroup: few rows (one per batch entry), so short slices fill the chip
 
 struct BudState {
   uint32_t prefix;       // digits found so far

@@ -9,8 +9,10 @@
 //   2. count: per wavefront segment, how many keys are above the threshold T / equal to it;
 //   3. write: prefix sums of those counts give every wavefront its output offset; a stable
 //      ballot compaction writes idx ascending and inv.
-// A head is cut into slices of 16384 tokens, one workgroup of 1024 threads per slice, so a
-// 128K-token layer with 32 heads runs 256 workgroups per kernel instead of 32.
+// A head is cut into slices (a power of two between 2048 and 16384 tokens, one workgroup of 1024
+// threads each), sized so that a launch has about 512 workgroups: each of the six small kernels
+// is a chain of dependent steps per thread, so it pays to spread it over the whole chip, but not
+// to go below a few tokens per thread.
 #include "tsa_internal.h"
 
 namespace tsa {
@@ -19,8 +21,7 @@ namespace {
 
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
-constexpr int kSlice = 16384;                 // tokens per workgroup
-constexpr int kSeg = kSlice / kWaves;         // tokens per wavefront (contiguous)
+constexpr int kMinSlice = 2048, kMaxSlice = 16384;   // tokens per workgroup (SelArgs::slice)
 
 struct SelState {
   uint32_t prefix;   // digits found so far, in place
@@ -41,6 +42,7 @@ struct SelArgs {
   RowWs* rows;
   uint2* counts;              // [row][nslices][kWaves] (n_gt, n_eq)
   int L, k, ff, fl, nslices;
+  int slice;                  // tokens per workgroup; a wavefront owns slice / kWaves contiguous tokens
 };
 
 // fp32 -> uint32 with the same order (-0 and +0 map to the same key)
@@ -112,8 +114,8 @@ __global__ __launch_bounds__(kThreads) void hist_kernel(SelArgs a) {
   __syncthreads();
   const uint32_t prefix = sh_state.prefix;
   constexpr uint32_t himask = PASS == 0 ? 0u : (0xffffffffu << (shift + 8));
-  const int t_end = min(a.L, (slice + 1) * kSlice);
-  for (int base = slice * kSlice; base < t_end; base += kThreads) {
+  const int t_end = min(a.L, (slice + 1) * a.slice);
+  for (int base = slice * a.slice; base < t_end; base += kThreads) {
     const int t = base + tid;
     bool valid = false;
     uint32_t dg = 0;
@@ -159,8 +161,9 @@ __global__ __launch_bounds__(kThreads) void count_kernel(SelArgs a) {
   }
   __syncthreads();
   const uint32_t T = sh_state.prefix;
-  const int t_lo = slice * kSlice + wave * kSeg;
-  const int t_hi = min(a.L, t_lo + kSeg);
+  const int seg = a.slice / kWaves;
+  const int t_lo = slice * a.slice + wave * seg;
+  const int t_hi = min(a.L, t_lo + seg);
   uint32_t n_gt = 0, n_eq = 0;
   for (int base = t_lo; base < t_hi; base += 64) {
     const int t = base + lane;
@@ -199,8 +202,9 @@ __global__ __launch_bounds__(kThreads) void write_kernel(SelArgs a) {
   }
   // ties are taken in token order until need_eq of them are used up
   uint32_t eq_run = eq_before, out_run = gt_before + min(need_eq, eq_before);
-  const int t_lo = slice * kSlice + wave * kSeg;
-  const int t_hi = min(a.L, t_lo + kSeg);
+  const int seg = a.slice / kWaves;
+  const int t_lo = slice * a.slice + wave * seg;
+  const int t_hi = min(a.L, t_lo + seg);
   const unsigned long long lt_mask = (1ull << lane) - 1ull;
   for (int base = t_lo; base < t_hi; base += 64) {
     const int t = base + lane;
@@ -333,7 +337,14 @@ __global__ void group_sum_kernel(const float* __restrict__ s, float* __restrict_
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int n_rows(const Dims& dm) { return dm.B * (dm.group_mode ? dm.Hkv : dm.Hq); }
-inline int n_slices(const Dims& dm) { return (dm.L + kSlice - 1) / kSlice; }
+// tokens per workgroup: the power of two that gives the launch about 512 workgroups
+inline int slice_for(const Dims& dm) {
+  const long long want = (long long)n_rows(dm) * dm.L / 512;
+  int s = kMinSlice;
+  while (s < kMaxSlice && s < want) s *= 2;
+  return s;
+}
+inline int n_slices(const Dims& dm) { return (dm.L + slice_for(dm) - 1) / slice_for(dm); }
 
 }  // namespace
 
@@ -359,6 +370,7 @@ hipError_t launch_select(const Dims& dm, const float* scores, int k_keep, int32_
   }
   a.idx = idx; a.inv = inv;
   a.L = dm.L; a.k = k_keep; a.ff = dm.force_first; a.fl = dm.force_last; a.nslices = n_slices(dm);
+  a.slice = slice_for(dm);
   if (dm.L <= kSmallL) {
     const size_t lds = ((size_t)dm.L + kWaves * 256) * sizeof(uint32_t);
     static bool attr_set = false;

@@ -112,6 +112,12 @@ def test_select_exact_ties(tsa):
         idx, inv = _run_select(tsa, s, k)
         widx, winv = orc.select(s, k)
         assert np.array_equal(idx, widx) and np.array_equal(inv, winv)
+    # rows cut into several slices (of 2048 and of 4096 tokens), ragged last slice, ties across slices
+    for rows, L, k, levels in ((2, 40001, 9000, 3), (16, 70000, 20000, 5)):
+        s = r.integers(0, levels, size=(1, rows, L)).astype(np.float32) * 0.25
+        idx, inv = _run_select(tsa, s, k)
+        widx, winv = orc.select(s, k)
+        assert np.array_equal(idx, widx) and np.array_equal(inv, winv)
     # signed zeros compare equal, negative scores order correctly
     s = np.array([[[-0.0, 0.0, -1.0, 0.0, -2.0, 5.0]]], dtype=np.float32)
     idx, _ = _run_select(tsa, s, 3)
