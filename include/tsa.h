@@ -167,7 +167,10 @@ int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void*
  *   residual [B,L,Hq*d] bf16 in/out or NULL: residual[b,t,h*d:(h+1)*d] += Oc[b,h,r,:] for
  *       t = idx[r] (fp32 add, one rounding to bf16); rows of unselected tokens are untouched.  This is
  *       the residual connection of Stage 2 with the identity in place of the output projection.
- * At least one of O, residual must be non-NULL. */
+ * At least one of O, residual must be non-NULL.  inv is required for O, idx for residual; idx may be
+ * NULL when only O is wanted (with both given, the copies can be driven by idx and the zero rows by
+ * inv as two independent streams, which is the faster form at moderate sparsity); idx and inv must be
+ * each other's inverse, as tsa_select writes them. */
 int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, const int32_t* inv,
                    int32_t k_keep, void* O, void* residual, void* stream);
 

@@ -263,7 +263,7 @@ int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, con
   if (O && (rc = check_ptr(inv, "inv"))) return rc;
   if (residual && (rc = check_ptr(idx, "idx"))) return rc;
   hipStream_t st = (hipStream_t)stream;
-  if (O && (rc = hip_status(tsa::launch_decompress(dm, Oc, inv, k_keep, O, st), "tsa_decompress"))) return rc;
+  if (O && (rc = hip_status(tsa::launch_decompress(dm, Oc, idx, inv, k_keep, O, st), "tsa_decompress"))) return rc;
   if (residual && (rc = hip_status(tsa::launch_residual(dm, Oc, idx, k_keep, residual, st), "tsa_decompress(residual)"))) return rc;
   return TSA_OK;
 }

@@ -66,7 +66,9 @@ hipError_t launch_drift(const void* h_in, const void* h_out, long long n_tokens,
 // gather_scatter.hip
 hipError_t launch_compress(const Dims& dm, const void* Q, const void* K, const void* V, const int32_t* idx,
                            int k_keep, void* Qc, void* Kc, void* Vc, hipStream_t st);
-hipError_t launch_decompress(const Dims& dm, const void* Oc, const int32_t* inv, int k_keep, void* O, hipStream_t st);
+// idx may be NULL (rows are then located through inv alone)
+hipError_t launch_decompress(const Dims& dm, const void* Oc, const int32_t* idx, const int32_t* inv, int k_keep, void* O,
+                             hipStream_t st);
 hipError_t launch_residual(const Dims& dm, const void* Oc, const int32_t* idx, int k_keep, void* residual, hipStream_t st);
 
 // The attention kernel reads V as tiled V^T: [B*kv_heads][ceil(Lc/kKeyTile)][d][kKeyTile] bf16 (one d-row

@@ -141,10 +141,12 @@ def test_select_forced_tokens_and_group_mode(tsa):
 
 # ------------------------------------------------------------------ compress / decompress
 
-@pytest.mark.parametrize("d,group_mode", [(128, 0), (64, 0), (128, 1)])
-def test_compress_decompress_bit_exact(tsa, d, group_mode):
-    r = _rng(300 + d + group_mode)
-    B, Hq, Hkv, L, k = 2, 6, 2, 777, 201
+# k = 201 of 777 rows kept: the two-stream scatter kernel (copies driven by idx, zeros by inv);
+# k = 60 and k = 700: the inv-driven kernel; both are also run without idx
+@pytest.mark.parametrize("d,group_mode,k", [(128, 0, 201), (64, 0, 201), (128, 1, 201), (128, 0, 60), (64, 1, 700)])
+def test_compress_decompress_bit_exact(tsa, d, group_mode, k):
+    r = _rng(300 + d + group_mode + k)
+    B, Hq, Hkv, L = 2, 6, 2, 777
     Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, L, d)), gu.rand_bits(r, (B, Hkv, L, d)), gu.rand_bits(r, (B, Hkv, L, d))
     Hs = Hkv if group_mode else Hq
     idx_np = np.stack([np.stack([np.sort(r.choice(L, k, replace=False)) for _ in range(Hs)]) for _ in range(B)]).astype(np.int32)
@@ -165,6 +167,9 @@ def test_compress_decompress_bit_exact(tsa, d, group_mode):
     O = torch.full((B, Hq, L, d), 7.0, dtype=torch.bfloat16, device=gu.DEV)
     tsa.tsa_decompress(desc, Qc, idx, inv, k, O=O)
     assert np.array_equal(gu.from_dev(O), orc.decompress(wq, idx_np, L))
+    O2 = torch.full((B, Hq, L, d), 7.0, dtype=torch.bfloat16, device=gu.DEV)
+    tsa.tsa_decompress(desc, Qc, None, inv, k, O=O2)                # without S_h: rows located through inv alone
+    assert torch.equal(O2, O)
     # residual mode
     xb = gu.rand_bits(r, (B, L, Hq * d))
     x = gu.to_dev(xb)
