@@ -545,6 +545,13 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
 #pragma unroll
     for (int c = 0; c < kChunks; ++c) {
       const int blk = c / CPB, i = c % CPB, slot = c % kRing;
+      // A wavefront in a block with exponentials has the longer chain of vector instructions between
+      // its MFMAs: it takes precedence over the other wavefront of its SIMD while it is there
+      // (measured: 3 % faster on random values, 5 % on zeros, against equal priorities).
+      if (i == 0) {
+        if (blk == 0 || blk == 2) __builtin_amdgcn_s_setprio(2);
+        else __builtin_amdgcn_s_setprio(0);
+      }
       // prefetch kPF chunks ahead; the first chunks of the next iteration read the rotated slots
       if (c + kPF < kChunks) fetch(c + kPF, kc, kn, vc);
       else fetch(c + kPF - kChunks, kn, kf, vn);
