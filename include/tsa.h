@@ -147,7 +147,7 @@ int tsa_compress(const tsa_desc* desc, const void* Q, const void* K, const void*
  *   tsa_desc.block_list_per_head): row qb lists, in ascending order and padded with -1,
  *   the key blocks that query block qb may see (composition with a block-sparse pattern in
  *   compacted index space, Section 1 / Appendix "other sparse attention methods").  Entries > qb
- *   are ignored; the diagonal block is causal inside.  block_size must be 128.
+ *   are ignored; the diagonal block is causal inside.  block_size: 64, 128 or 256.
  * The dense baseline is this same call with Qc=Q, Kc=K, Vc=V, Lc=L, kv_heads=Hkv.
  *   ws: tsa_attend_workspace_bytes(desc, Lc, kv_heads) bytes (only B, Hq, d of desc are used): the
  *   call first rewrites Vc into 64-key transposed tiles there, the layout the kernel's matrix

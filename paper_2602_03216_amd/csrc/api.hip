@@ -75,7 +75,8 @@ int hip_status(hipError_t e, const char* what) {
 
 int check_block_list(const int32_t* bl, int32_t block_size, int32_t max_blocks) {
   if (!bl) return TSA_OK;
-  if (block_size != 128) return fail(TSA_ERR_UNSUPPORTED, "block_size %d: only 128 is built", block_size);
+  if (block_size != 64 && block_size != 128 && block_size != 256)
+    return fail(TSA_ERR_UNSUPPORTED, "block_size %d: 64, 128 and 256 are built", block_size);
   if (max_blocks < 1) return fail(TSA_ERR_ARG, "max_blocks_per_row must be >= 1 with a block list");
   if (((uintptr_t)bl & 3u) != 0) return fail(TSA_ERR_ARG, "block_list is not 4-byte aligned");
   return TSA_OK;
@@ -249,7 +250,7 @@ int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void*
   hipStream_t st = (hipStream_t)stream;
   if ((rc = hip_status(tsa::launch_v_tiles(dm.B, kv_heads, Lc, dm.d, Vc, ws, st), "tsa_attend(V tiles)"))) return rc;
   return hip_status(tsa::launch_attend(dm.B, dm.Hq, kv_heads, Lc, dm.d, dm.scale, Qc, Kc, ws, block_list,
-                                       max_blocks_per_row, dm.block_list_per_head, Oc, lse, st), "tsa_attend");
+                                       block_size, max_blocks_per_row, dm.block_list_per_head, Oc, lse, st), "tsa_attend");
 }
 
 int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, const int32_t* inv,
@@ -291,8 +292,8 @@ int tsa_attend_fused(const tsa_desc* desc, const void* Q, const void* K, const v
   if ((rc = check_ptr(O, "O", true)) || (rc = check_ptr(Oc, "Oc", true)) || (rc = check_ptr(residual, "residual", true))) return rc;
   if (O && (rc = check_ptr(inv, "inv"))) return rc;
   if ((rc = check_block_list(block_list, block_size, max_blocks_per_row))) return rc;
-  return hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_keep, block_list, max_blocks_per_row, Oc, O,
-                                             residual, (hipStream_t)stream), "tsa_attend_fused");
+  return hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_keep, block_list, block_size, max_blocks_per_row,
+                                             Oc, O, residual, (hipStream_t)stream), "tsa_attend_fused");
 }
 
 int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* V, int32_t k_keep,
@@ -322,8 +323,8 @@ int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* 
   // V is gathered beforehand (into the transposed tiles the kernel's operands want).  The compacted
   // output is materialised only for the residual update.
   if ((rc = hip_status(tsa::launch_compress_tiled(dm, Q, K, V, idx, k_keep, nullptr, nullptr, Vt, st), "tsa_forward(V tiles)"))) return rc;
-  if ((rc = hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_keep, block_list, max_blocks_per_row,
-                                                nullptr, O, residual, st), "tsa_forward(attend)"))) return rc;
+  if ((rc = hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_keep, block_list, block_size,
+                                                max_blocks_per_row, nullptr, O, residual, st), "tsa_forward(attend)"))) return rc;
   if (idx_out) {
     const size_t Hs = (size_t)dm.B * (dm.group_mode ? dm.Hkv : dm.Hq);
     if ((rc = hip_status(hipMemcpyAsync(idx_out, idx, Hs * k_keep * sizeof(int32_t), hipMemcpyDeviceToDevice, st),

@@ -42,7 +42,7 @@ constexpr int BN = kKeyTile;   // keys per tile
 #define TSA_QS 1
 #endif
 constexpr int kQS = TSA_QS;    // query sub-tiles per wavefront (see attend_kernel)
-constexpr int kBlock = 128;    // block size of a block list (two key tiles, half a query tile)
+constexpr int kMaxLists = BM / BN;   // row blocks of a query tile at the smallest block size (64): 4
 constexpr float kNegBig = -1.0e30f;
 constexpr float kLazy = 8.0f;  // log2 units the running max may lag behind
 
@@ -55,6 +55,7 @@ struct AttendArgs {
   const int32_t* block_list;
   long long bl_head_stride;    // elements between the block lists of consecutive (b, h); 0 = one shared list
   int max_blocks;
+  int block;                   // block size of the list: 64, 128 or 256 tokens
   int BH, Hq, kvh, Lc, nq_tiles, nk_tiles;
   float c;                     // scale * log2(e)
   // Fused form (gather in the loads, scatter in the epilogue): Q and K are the ORIGINAL tensors of
@@ -108,41 +109,48 @@ constexpr int VS = BN + 8;
 __device__ __forceinline__ int k_row_perm(int lo) { return (lo & ~12) | ((lo & 4) << 1) | ((lo & 8) >> 1); }
 __device__ __forceinline__ int key_of(int r, int hi) { return 16 * (r >> 3) + 8 * hi + (r & 7); }
 
-// Key tiles a workgroup visits, in order.  `use` bit 0: the first 128 query rows of the
-// workgroup take part, bit 1: the last 128 (they can differ only under a block list).
+// Key tiles a workgroup visits, in order.  A block list cuts the workgroup's 256 query rows into
+// row blocks of `block` tokens (4, 2 or 1 of them); `use` bit j: row block j takes part in the tile
+// (they can differ only under a block list; plain causal attention is one row block of 256).
 struct Tile {
   int k0;      // first key of the tile, < 0: no more tiles
   int use;
 };
 
 struct TileGen {
-  const int32_t* la;
-  const int32_t* lb;
-  int ca, cb, ia, ib, sub, kb, use;
-  int a_cur, b_cur;            // next unread entry of each list (INT_MAX: exhausted)
+  const int32_t* list[kMaxLists];   // the lists of the workgroup's row blocks, merged on the fly
+  int cnt[kMaxLists], pos[kMaxLists];
+  int cur[kMaxLists];               // next unread entry of each list (INT_MAX: exhausted), read one block ahead
+  int n_lists, block, tiles_per_block, full;
+  int sub, kb, use;
   int plain_n, plain_i;
   bool plain;
   __device__ Tile next() {
     if (plain) {
       if (plain_i >= plain_n) return Tile{-1, 0};
-      Tile t{plain_i * BN, 3};
+      Tile t{plain_i * BN, 1};
       ++plain_i;
       return t;
     }
     if (sub == 0) {
-      // a_cur / b_cur were read from the lists when the previous block was handed out, two tiles
-      // ago: the look-up is never waited for
-      const int a = a_cur, b = b_cur;
-      kb = min(a, b);
+      // cur[] was read from the lists when the previous block was handed out, at least a tile ago:
+      // the look-up is never waited for
+      kb = INT_MAX;
+#pragma unroll
+      for (int j = 0; j < kMaxLists; ++j) kb = min(kb, cur[j]);
       if (kb == INT_MAX) return Tile{-1, 0};
-      use = (a == kb ? 1 : 0) | (b == kb ? 2 : 0);
-      if (a == kb) { ++ia; a_cur = ia < ca ? la[ia] : INT_MAX; }
-      if (b == kb) { ++ib; b_cur = ib < cb ? lb[ib] : INT_MAX; }
-      sub = 1;
-      return Tile{kb * kBlock, use};
+      use = 0;
+#pragma unroll
+      for (int j = 0; j < kMaxLists; ++j)
+        if (cur[j] == kb) {
+          use |= 1 << j;
+          ++pos[j];
+          cur[j] = pos[j] < cnt[j] ? list[j][pos[j]] : INT_MAX;
+        }
     }
-    sub = 0;
-    return Tile{kb * kBlock + BN, use};
+    const Tile t{kb * block + sub * BN, use};
+    sub = sub + 1 == tiles_per_block ? 0 : sub + 1;
+    return t;
   }
 };
 
@@ -313,7 +321,8 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int q0 = qt * BM;
   const int wrow0 = q0 + RW * wave;                      // first query row of this wavefront
-  const int half_bit = 1 << ((RW * wave) / kBlock);      // which 128-row half the wavefront is in
+  const int row_block = a.block_list ? a.block : BM;
+  const int half_bit = 1 << ((RW * wave) / row_block);   // which row block of the query tile the wavefront is in
   const float c = a.c;
   const float c_ = c;
 
@@ -369,26 +378,37 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   gen.plain = a.block_list == nullptr;
   gen.plain_i = 0;
   gen.plain_n = (min(q0 + BM, a.Lc) + BN - 1) / BN;
-  gen.ia = gen.ib = gen.sub = gen.kb = gen.use = gen.ca = gen.cb = 0;
-  gen.a_cur = gen.b_cur = INT_MAX;
-  gen.la = gen.lb = nullptr;
+  gen.sub = gen.kb = gen.use = 0;
+  gen.n_lists = 1;
+  gen.block = BM;
+  gen.tiles_per_block = BM / BN;
+  gen.full = 1;
+  int longest_list = 0;
+#pragma unroll
+  for (int j = 0; j < kMaxLists; ++j) { gen.list[j] = nullptr; gen.cnt[j] = gen.pos[j] = 0; gen.cur[j] = INT_MAX; }
   if (!gen.plain) {
-    const int nqb = (a.Lc + kBlock - 1) / kBlock;
-    const int qa = 2 * qt, qb = 2 * qt + 1;
+    gen.block = a.block;
+    gen.n_lists = BM / a.block;
+    gen.tiles_per_block = a.block / BN;
+    gen.full = 0;
+    const int nqb = (a.Lc + a.block - 1) / a.block;
     const int32_t* bl = a.block_list + bh * a.bl_head_stride;
-    gen.la = bl + (long long)qa * a.max_blocks;
-    gen.ca = count_valid(gen.la, a.max_blocks, qa);
-    if (qb < nqb) {
-      gen.lb = bl + (long long)qb * a.max_blocks;
-      gen.cb = count_valid(gen.lb, a.max_blocks, qb);
+#pragma unroll
+    for (int j = 0; j < kMaxLists; ++j) {
+      const int qb = qt * gen.n_lists + j;
+      if (j < gen.n_lists && qb < nqb) {
+        gen.list[j] = bl + (long long)qb * a.max_blocks;
+        gen.cnt[j] = count_valid(gen.list[j], a.max_blocks, qb);
+        if (gen.cnt[j] > 0) gen.cur[j] = gen.list[j][0];
+        gen.full |= 1 << j;
+        longest_list = max(longest_list, gen.cnt[j]);
+      }
     }
-    if (gen.ca > 0) gen.a_cur = gen.la[0];
-    if (gen.cb > 0) gen.b_cur = gen.lb[0];
   }
 
   // zero rows: as evenly over the pipelined iterations as their number allows
   if (zfill) {
-    const int n_pipelined = gen.plain ? q0 / BN - 1 : 2 * max(gen.ca, gen.cb) - 6;
+    const int n_pipelined = gen.plain ? q0 / BN - 1 : gen.tiles_per_block * longest_list - 6;
     z_every = max(1, n_pipelined / max(1, z_passes));
   }
 
@@ -634,7 +654,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   // tile but the last five; sink + window lists: all but the first and last few); diagonal tiles,
   // tiles only one half visits and the tile in front of either take the general iteration, with
   // masks and per-wavefront decisions.  Both keep the same invariant, so they alternate freely.
-  auto pipelined = [&](const Tile& t) -> bool { return t.k0 >= 0 && t.use == 3 && t.k0 + BN <= q0; };
+  auto pipelined = [&](const Tile& t) -> bool { return t.k0 >= 0 && t.use == gen.full && t.k0 + BN <= q0; };
   while (T0.k0 >= 0) {
     if (pipelined(T0) && pipelined(T1)) {
       prime_ring();
@@ -736,10 +756,11 @@ hipError_t launch_any(AttendArgs& a, int d, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
-                         const void* Vt, const int32_t* block_list, int max_blocks_per_row, int block_list_per_head,
-                         void* Oc, float* lse, hipStream_t st) {
+                         const void* Vt, const int32_t* block_list, int block_size, int max_blocks_per_row,
+                         int block_list_per_head, void* Oc, float* lse, hipStream_t st) {
   AttendArgs a;
-  a.bl_head_stride = block_list_per_head ? (long long)((Lc + kBlock - 1) / kBlock) * max_blocks_per_row : 0;
+  a.block = block_list ? block_size : BM;
+  a.bl_head_stride = block_list_per_head ? (long long)((Lc + a.block - 1) / a.block) * max_blocks_per_row : 0;
   a.Q = (const __bf16*)Qc; a.K = (const __bf16*)Kc; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
   a.lse = lse; a.block_list = block_list; a.max_blocks = max_blocks_per_row;
   a.BH = B * Hq; a.Hq = Hq; a.kvh = kv_heads; a.Lc = Lc;
@@ -749,12 +770,13 @@ hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale
 }
 
 hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, const void* Vt, const int32_t* idx,
-                               const int32_t* inv, int k_keep, const int32_t* block_list, int max_blocks_per_row,
-                               void* Oc, void* O, void* residual, hipStream_t st) {
+                               const int32_t* inv, int k_keep, const int32_t* block_list, int block_size,
+                               int max_blocks_per_row, void* Oc, void* O, void* residual, hipStream_t st) {
   AttendArgs a;
+  a.block = block_list ? block_size : BM;
   a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
   a.lse = nullptr; a.block_list = block_list; a.max_blocks = max_blocks_per_row;
-  a.bl_head_stride = dm.block_list_per_head ? (long long)((k_keep + kBlock - 1) / kBlock) * max_blocks_per_row : 0;
+  a.bl_head_stride = dm.block_list_per_head ? (long long)((k_keep + a.block - 1) / a.block) * max_blocks_per_row : 0;
   a.BH = dm.B * dm.Hq; a.Hq = dm.Hq; a.kvh = dm.group_mode ? dm.Hkv : dm.Hq; a.Lc = k_keep;
   a.c = dm.scale * kLog2e;
   a.idx = idx; a.inv = inv; a.Of = (__bf16*)O; a.X = (__bf16*)residual; a.L = dm.L; a.Hkv = dm.Hkv;

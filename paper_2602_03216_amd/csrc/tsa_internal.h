@@ -86,8 +86,8 @@ hipError_t launch_compress_tiled(const Dims& dm, const void* Q, const void* K, c
 
 // attend.hip
 hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
-                         const void* Vt, const int32_t* block_list, int max_blocks_per_row, int block_list_per_head,
-                         void* Oc, float* lse, hipStream_t st);
+                         const void* Vt, const int32_t* block_list, int block_size, int max_blocks_per_row,
+                         int block_list_per_head, void* Oc, float* lse, hipStream_t st);
 
 // attend.hip, fused form used by tsa_forward: Q and K are the original tensors, rows are gathered
 // through idx inside the kernel's loads; Vt = tiles of the gathered V (launch_compress_tiled with
@@ -95,8 +95,8 @@ hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale
 // epilogue and zeros elsewhere; Oc [B,Hq,k,d] (may be NULL) the compacted output; residual [B,L,Hq*d]
 // (may be NULL) gets the output rows added in place.
 hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, const void* Vt, const int32_t* idx,
-                               const int32_t* inv, int k_keep, const int32_t* block_list, int max_blocks_per_row,
-                               void* Oc, void* O, void* residual, hipStream_t st);
+                               const int32_t* inv, int k_keep, const int32_t* block_list, int block_size,
+                               int max_blocks_per_row, void* Oc, void* O, void* residual, hipStream_t st);
 
 // probe.hip: bare MFMA loop, 8 * iters MFMAs per wavefront, 4 wavefronts per workgroup
 hipError_t launch_mfma_probe(const void* operands, int iters, int blocks, float* sink, long long* clocks, hipStream_t st);

@@ -235,10 +235,11 @@ def test_attend_large_logits_and_scale(tsa):
 
 # (3000, 1024): long stretches of pipelined iterations between the sink block, the window's first
 # block (visited by half of the workgroup only) and the diagonal
-@pytest.mark.parametrize("Lc,window", [(1000, 256), (1300, 128), (640, 4096), (3000, 1024)])
-def test_attend_block_list(tsa, Lc, window):
-    r = _rng(500 + Lc)
-    B, Hq, Hk, d, Bs = 1, 4, 2, 128, 128
+@pytest.mark.parametrize("Lc,window,Bs", [(1000, 256, 128), (1300, 128, 128), (640, 4096, 128), (3000, 1024, 128),
+                                          (1000, 256, 64), (2100, 512, 64), (1500, 512, 256), (3000, 1024, 256)])
+def test_attend_block_list(tsa, Lc, window, Bs):
+    r = _rng(500 + Lc + Bs)
+    B, Hq, Hk, d = 1, 4, 2, 128
     Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d))
     bl = orc.lambda_block_list(Lc, Bs, window, 1)
     desc = tsa.make_desc(B, Hq, Hk, Lc, d, 1)
@@ -334,12 +335,14 @@ def test_fused_path_equals_the_separate_calls(tsa, B, Hq, Hkv, L, d, k, group_mo
     assert torch.equal(O2, O1) and torch.equal(O3, O1)
 
 
-@pytest.mark.parametrize("Hq,Hk,Lc,d", [(4, 2, 1000, 128), (3, 3, 1500, 64), (2, 1, 2600, 128)])
-def test_attend_per_head_block_lists(tsa, Hq, Hk, Lc, d):
-    """Block-sparse composition with a different pattern for every head (vertical + slash)."""
+@pytest.mark.parametrize("Hq,Hk,Lc,d,Bs", [(4, 2, 1000, 128, 128), (3, 3, 1500, 64, 128), (2, 1, 2600, 128, 128),
+                                           (4, 2, 1100, 128, 64), (2, 2, 1900, 64, 256)])
+def test_attend_per_head_block_lists(tsa, Hq, Hk, Lc, d, Bs):
+    """Block-sparse composition with a different pattern for every head (vertical + slash), in blocks
+    of 64, 128 and 256 tokens."""
     from paper_2602_03216_amd import inputs as gen
     r = _rng(1500 + Lc)
-    B, Bs = 2, 128
+    B = 2
     Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d))
     bl = gen.vertical_slash_block_lists(B, Hq, (Lc + Bs - 1) // Bs, seed=Lc)
     desc = tsa.make_desc(B, Hq, Hk, Lc, d, 1, block_list_per_head=1)
@@ -350,12 +353,13 @@ def test_attend_per_head_block_lists(tsa, Hq, Hk, Lc, d):
     gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(per-head block lists)")
 
 
-def test_forward_with_per_head_block_lists(tsa):
+@pytest.mark.parametrize("Bs", [128, 64, 256])
+def test_forward_with_per_head_block_lists(tsa, Bs):
     """Token selection first, then a per-head block-sparse pattern in compacted space: the whole layer
     against the oracle's."""
     from paper_2602_03216_amd import inputs as gen
     from tests.margin import enforce_margin
-    Hq, Hkv, L, d, Lq, k, Bs = 4, 2, 2000, 128, 64, 900, 128
+    Hq, Hkv, L, d, Lq, k = 4, 2, 2000, 128, 64, 900
     cfg = dict(id=91, name="small", B=1, Hq=Hq, Hkv=Hkv, L=L, d=d, last_q=Lq, plant="direction", n_plant=20, norm_factor=3.0,
                frac_plant=0.1, boost=4.0, sink_boost=6.0, n_sink=4, zipf_a=1.2)
     inp = gen.make_inputs(cfg, seed=1234)
