@@ -70,7 +70,7 @@ def test_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert lib.tsa_compress(dp, fake, fake, fake, None, 16, fake, fake, fake, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_attend(dp, fake, fake, fake, 0, 4, None, 0, 0, fake, None, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_attend(dp, fake, fake, fake, 16, 3, None, 0, 0, fake, None, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
-    assert lib.tsa_attend(dp, fake, fake, fake, 256, 4, fake, 64, 3, fake, None, fake, 1 << 30, None) == tsa.TSA_ERR_UNSUPPORTED
+    assert lib.tsa_attend(dp, fake, fake, fake, 256, 4, fake, 32, 3, fake, None, fake, 1 << 30, None) == tsa.TSA_ERR_UNSUPPORTED    # blocks of 64, 128, 256 only
     assert lib.tsa_attend(dp, fake, fake, fake, 256, 4, None, 0, 0, fake, None, fake, 64, None) == tsa.TSA_ERR_WORKSPACE
     assert tsa.tsa_attend_workspace_bytes(d, 100, 4) == 4 * 128 * 64 * 2 and tsa.tsa_attend_workspace_bytes(d, 100, 3) == 0
     assert lib.tsa_decompress(dp, fake, fake, fake, 16, None, None, None) == tsa.TSA_ERR_ARG
