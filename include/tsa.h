@@ -153,7 +153,11 @@ int tsa_compress(const tsa_desc* desc, const void* Q, const void* K, const void*
  *   call first rewrites Vc into 64-key transposed tiles there, the layout the kernel's matrix
  *   operands want; Vc itself is not modified.
  * Arithmetic: bf16 MFMA with fp32 accumulation, online softmax in fp32, probabilities rounded
- * to bf16 before the PV product, output rounded to bf16 (nearest even). */
+ * to bf16 before the PV product, output rounded to bf16 (nearest even).  The queries enter the
+ * QK product as Qc * (scale * log2 e) rounded to bf16 (nearest even), so that the products come
+ * out in the units of the base-2 exponential: one rounding of relative size 2^-9 per query
+ * element, of the same size as the one that made Qc bf16 in the first place; a logit moves by
+ * about 2^-9 / sqrt(3) * scale * |q_i k_i|_2 (1e-3 for unit-variance rows). */
 size_t tsa_attend_workspace_bytes(const tsa_desc* desc, int32_t Lc, int32_t kv_heads);
 int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void* Vc,
                int32_t Lc, int32_t kv_heads,

@@ -21,6 +21,10 @@
 // The O rescale is lazy: the running max is only raised when a row's new max exceeds it by
 // more than 2^8, so most tiles skip the multiply over the whole accumulator; the final
 // division by the row sum makes the result independent of the max actually used.
+// The exponent s * scale * log2(e) - m costs no vector instruction in the pipelined loop: Q is
+// multiplied by scale * log2(e) once when it is loaded (and rounded back to bf16, one more rounding
+// of relative size 2^-9 on the query side), and the first MFMA of every QK chain starts from the
+// accumulator -m instead of 0, so the chain delivers s - m and the loop applies exp2 to it directly.
 // The template also holds the layout with 64 rows per wavefront (QS = 2: four wavefronts, one
 // per SIMD, every LDS fragment feeds two MFMAs); it measures slower and is not instantiated
 // by default.
@@ -231,6 +235,32 @@ __device__ __forceinline__ void raise_max(const float (&mxc)[QS], float (&m)[QS]
   }
 }
 
+// The same for a half tile held as s - m (the pipelined iteration subtracts the running max inside
+// the MFMA chain): mx is the row max relative to m.  A raise also shifts the pending half tile and
+// the chain-start vector negm (16 copies of -m, the C operand of the first MFMA of a chain).
+template <int ND, int QS>
+__device__ __forceinline__ void raise_max_rel(const float (&mx)[QS], float (&m)[QS], f32x16 (&negm)[QS], float (&l)[QS],
+                                              f32x16 (&o)[QS][ND], f32x16 (&pending)[QS]) {
+  bool grow = false;
+#pragma unroll
+  for (int qs = 0; qs < QS; ++qs) grow = grow || mx[qs] > kLazy;
+  if (__any(grow)) {
+#pragma unroll
+    for (int qs = 0; qs < QS; ++qs) {
+      const float dlt = fmaxf(mx[qs], 0.f);
+      const float alpha = fast_exp2(-dlt);
+      m[qs] += dlt;
+      l[qs] *= alpha;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { negm[qs][r] = -m[qs]; pending[qs][r] -= dlt; }
+#pragma unroll
+      for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[qs][dt][r] *= alpha;
+    }
+  }
+}
+
 template <int ND, int QS>
 __device__ __forceinline__ void softmax_max(const f32x16 (&s)[QS], float c, float (&m)[QS], float (&l)[QS], f32x16 (&o)[QS][ND]) {
   float mxc[QS];
@@ -238,7 +268,8 @@ __device__ __forceinline__ void softmax_max(const f32x16 (&s)[QS], float c, floa
   raise_max<ND, QS>(mxc, m, l, o);
 }
 
-// p = exp2(s*c - m), packed to bf16 pairs in accumulator order; row sums into l.
+// p = exp2(s*c - m), packed to bf16 pairs in accumulator order; row sums into l.  (c is 1 in the
+// kernel, whose scores come out of the MFMAs already scaled.)
 template <int QS>
 __device__ __forceinline__ void softmax_exp(const f32x16 (&s)[QS], float c, const float (&m)[QS], float (&l)[QS], uint32_t (&pb)[QS][8]) {
 #pragma unroll
@@ -323,8 +354,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const int wrow0 = q0 + RW * wave;                      // first query row of this wavefront
   const int row_block = a.block_list ? a.block : BM;
   const int half_bit = 1 << ((RW * wave) / row_block);   // which row block of the query tile the wavefront is in
-  const float c = a.c;
-  const float c_ = c;
+  const float c = 1.0f;                                  // the scores are already in exponent units (scaled Q)
 
   // ---- fused form: zero rows of the full-length output.  The workgroup owns the tokens from its
   // first selected token up to the next workgroup's first one (the first workgroup of a head starts
@@ -373,6 +403,14 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   // loads as "possibly pending" into the main loop and makes every MFMA that reads a Q fragment
   // wait for the oldest in-flight K/V prefetch as well.
   __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0)
+  // Q is scaled by scale * log2(e) here, once, and rounded back to bf16: the scores then leave the
+  // MFMAs in the units of the exponent and the loop spends no multiplication on them.
+#pragma unroll
+  for (int qs = 0; qs < QS; ++qs)
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[qs][s][e] = (__bf16)((float)qf[qs][s][e] * a.c);
 
   TileGen gen;
   gen.plain = a.block_list == nullptr;
@@ -531,6 +569,9 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   //    8..15  O^T += V^T(T0, half 0) pA  with  row max of sB          [then the rare raise of m]
   //   16..23  S^T(T1, half 0) -> sA      with  exp(sB) -> pB
   //   24..31  O^T += V^T(T0, half 1) pB  with  row max of sA, staging  [barrier, rare raise of m]
+  // Inside this loop sA and sB hold s - m (the QK chains start from -m), so the exponent is the
+  // accumulator itself and the row max is relative to m; a raise of m between the chain and its
+  // exponentials shifts the pending half tile by the same amount.
   // Each chunk consumes one 16-byte LDS fragment per lane (a K fragment or a V^T fragment);
   // fragments are fetched kPF chunks ahead through a small register ring that runs across the
   // blocks and across iterations, so the LDS latency is hidden.
@@ -559,6 +600,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   };
   // vload: byte offset of the V tile to prefetch (tile T2), tokload: first compacted row of the
   // K tile whose rows are looked up (tile T4)
+  f32x16 negm[QS];
   auto fast_iter = [&](const int vload, const int tokload) {
     float mxc[QS], mx[QS], ps0[QS], ps1[QS];
     f32x16 acc[QS];
@@ -583,15 +625,15 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
         // shadow of the MFMA that was just issued
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
-          if (i == 0) { acc[qs] = f32x16{0}; ps0[qs] = ps1[qs] = 0.f; }
+          if (i == 0) acc[qs] = negm[qs];
           acc[qs] = mfma32(kfr[slot], qf[qs][i], acc[qs]);
 #pragma unroll
           for (int e = 0; e < EPS; e += 2) {
             const int r = EPS * i + e;
-            const float p0 = fast_exp2(fmaf(s_in[qs][r], c_, -m[qs]));
-            const float p1 = fast_exp2(fmaf(s_in[qs][r + 1], c_, -m[qs]));
-            ps0[qs] += p0;
-            ps1[qs] += p1;
+            const float p0 = fast_exp2(s_in[qs][r]);
+            const float p1 = fast_exp2(s_in[qs][r + 1]);
+            if (r == 0) { ps0[qs] = p0; ps1[qs] = p1; }
+            else { ps0[qs] += p0; ps1[qs] += p1; }
             p_out[qs][r >> 1] = pack_bf16(p0, p1);
           }
           if (qs + 1 < QS) __builtin_amdgcn_sched_barrier(0);
@@ -638,14 +680,14 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
         }
         if (i == CPB - 1) {
 #pragma unroll
-          for (int qs = 0; qs < QS; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32)) * c_;
+          for (int qs = 0; qs < QS; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32));
         }
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (c == 2 * CPB - 1) raise_max<ND, QS>(mxc, m, l, o);
+      if (c == 2 * CPB - 1) raise_max_rel<ND, QS>(mxc, m, negm, l, o, sB);
     }
     lds_barrier();
-    raise_max<ND, QS>(mxc, m, l, o);
+    raise_max_rel<ND, QS>(mxc, m, negm, l, o, sA);
     rotate();
     };
 
@@ -657,6 +699,11 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   auto pipelined = [&](const Tile& t) -> bool { return t.k0 >= 0 && t.use == gen.full && t.k0 + BN <= q0; };
   while (T0.k0 >= 0) {
     if (pipelined(T0) && pipelined(T1)) {
+      // the pipelined iterations hold their half tiles as s - m: sA enters and leaves in that form
+#pragma unroll
+      for (int qs = 0; qs < QS; ++qs)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { negm[qs][r] = -m[qs]; sA[qs][r] -= m[qs]; }
       prime_ring();
       do {
         const Tile T4 = gen.next();
@@ -665,6 +712,10 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
         T0 = T1; T1 = T2; T2 = T3; T3 = T4;
       } while (pipelined(T0) && pipelined(T1));
       if (T0.k0 < 0) break;
+#pragma unroll
+      for (int qs = 0; qs < QS; ++qs)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sA[qs][r] += m[qs];
     }
     qk_half<D, QS>(kc + 32 * KS, k_rd, qf, sB);
     if (wave_active(T0)) {
