@@ -249,6 +249,27 @@ def test_attend_large_logits_and_scale(tsa):
     assert err.max() <= 0.35 and err.mean() <= 1e-2
 
 
+def test_attend_logits_growing_along_the_keys(tsa):
+    """Keys grow along the sequence (logit of key c about 0.066 c nats, 190 log2 units over the row):
+    the running max is raised every tile or two, in the middle of the pipelined iterations, where the
+    half tile that waits for its exponentials has to be shifted together with the accumulator."""
+    r = _rng(23)
+    B, H, Lc, d = 1, 2, 2000, 128
+    u = np.ones(d) / np.sqrt(d)
+    q = 6.0 * u + 0.3 * r.standard_normal((B, H, Lc, d))
+    k = (np.arange(Lc)[None, None, :, None] / 8.0) * u + 0.3 * r.standard_normal((B, H, Lc, d))
+    Qb, Kb, Vb = orc.f64_to_bf16(q), orc.f64_to_bf16(k), gu.rand_bits(r, (B, H, Lc, d))
+    desc = tsa.make_desc(B, H, H, Lc, d, 1)
+    O = torch.empty((B, H, Lc, d), dtype=torch.bfloat16, device=gu.DEV)
+    lse = torch.zeros((B, H, Lc), dtype=torch.float32, device=gu.DEV)
+    tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, H, O, tsa.alloc_attend_workspace(desc, Lc, H, gu.DEV), lse)
+    want, wlse = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), return_lse=True)
+    gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(growing logits)")
+    # the log-sum-exp follows the largest logits (up to 130 nats here), which the rounding of the scaled
+    # queries moves by up to 2^-9 of their size
+    assert np.abs(lse.cpu().numpy() - wlse).max() < 130 * 2.0 ** -9 + 6e-3
+
+
 # (3000, 1024): long stretches of pipelined iterations between the sink block, the window's first
 # block (visited by half of the workgroup only) and the diagonal
 @pytest.mark.parametrize("Lc,window,Bs", [(1000, 256, 128), (1300, 128, 128), (640, 4096, 128), (3000, 1024, 128),
