@@ -60,6 +60,7 @@ struct AttendArgs {
   long long bl_head_stride;    // elements between the block lists of consecutive (b, h); 0 = one shared list
   int max_blocks;
   int block;                   // block size of the list: 64, 128 or 256 tokens
+  int exact;                   // 1: scores scaled in fp32 (host side only: selects the kernel)
   int BH, Hq, kvh, Lc, nq_tiles, nk_tiles;
   float c;                     // scale * log2(e)
   // Fused form (gather in the loads, scatter in the epilogue): Q and K are the ORIGINAL tensors of
@@ -307,7 +308,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const __bf16* base, 
 // every LDS fragment feeds two MFMAs.  QS = 1: 8 wavefronts of 32 rows, two per SIMD, which share
 // the SIMD's issue slots (a lone wavefront issues one vector instruction every ~8 clocks, two
 // together one every ~5) at the price of one LDS fragment per MFMA.
-template <int D, int QS, bool FUSED>
+// SCALED_Q: Q is multiplied by scale * log2(e) and rounded to bf16 when it is loaded, and the pipelined
+// iteration holds its half tiles as s - m (see the head of the file); otherwise the products are scaled
+// in fp32 by an fma in front of every exp2.
+template <int D, int QS, bool FUSED, bool SCALED_Q>
 __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) {
   constexpr int kThreads = 512 / QS;
   constexpr int RW = 32 * QS;                     // query rows per wavefront
@@ -354,7 +358,8 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const int wrow0 = q0 + RW * wave;                      // first query row of this wavefront
   const int row_block = a.block_list ? a.block : BM;
   const int half_bit = 1 << ((RW * wave) / row_block);   // which row block of the query tile the wavefront is in
-  const float c = 1.0f;                                  // the scores are already in exponent units (scaled Q)
+  const float c = SCALED_Q ? 1.0f : a.c;                 // scaled Q: the scores are already in exponent units
+  const float c_ = c;                                    // (the chunk loop of the pipelined iteration has its own c)
 
   // ---- fused form: zero rows of the full-length output.  The workgroup owns the tokens from its
   // first selected token up to the next workgroup's first one (the first workgroup of a head starts
@@ -405,6 +410,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0)
   // Q is scaled by scale * log2(e) here, once, and rounded back to bf16: the scores then leave the
   // MFMAs in the units of the exponent and the loop spends no multiplication on them.
+  if (SCALED_Q)
 #pragma unroll
   for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
@@ -625,13 +631,13 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
         // shadow of the MFMA that was just issued
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
-          if (i == 0) acc[qs] = negm[qs];
+          if (i == 0) acc[qs] = SCALED_Q ? negm[qs] : f32x16{0};
           acc[qs] = mfma32(kfr[slot], qf[qs][i], acc[qs]);
 #pragma unroll
           for (int e = 0; e < EPS; e += 2) {
             const int r = EPS * i + e;
-            const float p0 = fast_exp2(s_in[qs][r]);
-            const float p1 = fast_exp2(s_in[qs][r + 1]);
+            const float p0 = SCALED_Q ? fast_exp2(s_in[qs][r]) : fast_exp2(fmaf(s_in[qs][r], c_, -m[qs]));
+            const float p1 = SCALED_Q ? fast_exp2(s_in[qs][r + 1]) : fast_exp2(fmaf(s_in[qs][r + 1], c_, -m[qs]));
             if (r == 0) { ps0[qs] = p0; ps1[qs] = p1; }
             else { ps0[qs] += p0; ps1[qs] += p1; }
             p_out[qs][r >> 1] = pack_bf16(p0, p1);
@@ -680,14 +686,18 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
         }
         if (i == CPB - 1) {
 #pragma unroll
-          for (int qs = 0; qs < QS; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32));
+          for (int qs = 0; qs < QS; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32)) * c_;
         }
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (c == 2 * CPB - 1) raise_max_rel<ND, QS>(mxc, m, negm, l, o, sB);
+      if (c == 2 * CPB - 1) {
+        if (SCALED_Q) raise_max_rel<ND, QS>(mxc, m, negm, l, o, sB);
+        else raise_max<ND, QS>(mxc, m, l, o);
+      }
     }
     lds_barrier();
-    raise_max_rel<ND, QS>(mxc, m, negm, l, o, sA);
+    if (SCALED_Q) raise_max_rel<ND, QS>(mxc, m, negm, l, o, sA);
+    else raise_max<ND, QS>(mxc, m, l, o);
     rotate();
     };
 
@@ -700,6 +710,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   while (T0.k0 >= 0) {
     if (pipelined(T0) && pipelined(T1)) {
       // the pipelined iterations hold their half tiles as s - m: sA enters and leaves in that form
+      if (SCALED_Q)
 #pragma unroll
       for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
@@ -712,6 +723,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
         T0 = T1; T1 = T2; T2 = T3; T3 = T4;
       } while (pipelined(T0) && pipelined(T1));
       if (T0.k0 < 0) break;
+      if (SCALED_Q)
 #pragma unroll
       for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
@@ -799,8 +811,13 @@ hipError_t launch_any(AttendArgs& a, int d, hipStream_t st) {
   a.nq_tiles = (a.Lc + BM - 1) / BM;
   a.nk_tiles = (a.Lc + BN - 1) / BN;
   const unsigned grid = 8u * (unsigned)((a.BH + 7) / 8) * (unsigned)a.nq_tiles;
-  if (d == 128) attend_kernel<128, kQS, FUSED><<<grid, 512 / kQS, 0, st>>>(a);
-  else attend_kernel<64, kQS, FUSED><<<grid, 512 / kQS, 0, st>>>(a);
+  if (a.exact) {
+    if (d == 128) attend_kernel<128, kQS, FUSED, false><<<grid, 512 / kQS, 0, st>>>(a);
+    else attend_kernel<64, kQS, FUSED, false><<<grid, 512 / kQS, 0, st>>>(a);
+  } else {
+    if (d == 128) attend_kernel<128, kQS, FUSED, true><<<grid, 512 / kQS, 0, st>>>(a);
+    else attend_kernel<64, kQS, FUSED, true><<<grid, 512 / kQS, 0, st>>>(a);
+  }
   return hipGetLastError();
 }
 
@@ -808,8 +825,9 @@ hipError_t launch_any(AttendArgs& a, int d, hipStream_t st) {
 
 hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
                          const void* Vt, const int32_t* block_list, int block_size, int max_blocks_per_row,
-                         int block_list_per_head, void* Oc, float* lse, hipStream_t st) {
+                         int block_list_per_head, int exact_scale, void* Oc, float* lse, hipStream_t st) {
   AttendArgs a;
+  a.exact = exact_scale;
   a.block = block_list ? block_size : BM;
   a.bl_head_stride = block_list_per_head ? (long long)((Lc + a.block - 1) / a.block) * max_blocks_per_row : 0;
   a.Q = (const __bf16*)Qc; a.K = (const __bf16*)Kc; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
@@ -824,6 +842,7 @@ hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, con
                                const int32_t* inv, int k_keep, const int32_t* block_list, int block_size,
                                int max_blocks_per_row, void* Oc, void* O, void* residual, hipStream_t st) {
   AttendArgs a;
+  a.exact = dm.exact_scale;
   a.block = block_list ? block_size : BM;
   a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
   a.lse = nullptr; a.block_list = block_list; a.max_blocks = max_blocks_per_row;
