@@ -25,6 +25,8 @@
 // multiplied by scale * log2(e) once when it is loaded (and rounded back to bf16, one more rounding
 // of relative size 2^-9 on the query side), and the first MFMA of every QK chain starts from the
 // accumulator -m instead of 0, so the chain delivers s - m and the loop applies exp2 to it directly.
+// (Template flag SCALED_Q; tsa_desc.exact_scale selects the instantiation without it, which scales the
+// products in fp32 with an fma in front of every exp2.)
 // The template also holds the layout with 64 rows per wavefront (QS = 2: four wavefronts, one
 // per SIMD, every LDS fragment feeds two MFMAs); it measures slower and is not instantiated
 // by default.
