@@ -327,7 +327,7 @@ def main():
         "speedup_attend_vs_own_dense": head["speedup_attend_vs_dense"],
         "ideal_attend_speedup": head["ideal_attend_speedup"],
         "dense_ms": r128["dense_ms"],
-        "roofline": {"kernel": "attend_kernel<128, 1, true> (tsa_attend_fused: the attention launch of tsa_forward)",
+        "roofline": {"kernel": "attend_kernel<128, 1, true, true> (tsa_attend_fused: the attention launch of tsa_forward; template arguments: d, query sub-tiles per wavefront, fused gather/scatter, scaled queries)",
                      "bound": "mfma", "achieved": head["attend_fused_tflops"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": head["attend_fused_frac_mfma_peak"],
                      "flops_per_launch": w["attend_flops"], "avg_launch_ms": head["attend_fused_ms"],
