@@ -217,6 +217,24 @@ int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* 
                 void* O, void* residual, int32_t* idx_out,
                 void* ws, size_t ws_bytes, void* stream);
 
+/* The layer with Dynamic Token Coverage (Section 2.3, Algorithm 1 in full) on one stream, no host
+ * synchronisation: score -> coverage budget -> select -> compress -> attend -> decompress.  The number
+ * of kept tokens is decided on the device, per batch entry, from the cross-head mass threshold
+ * tau_cov (as tsa_coverage_budget), clamped to k_max; every launch is sized for k_max and reads the
+ * count it works on from device memory, so the call can be recorded into a HIP graph.  The result
+ * equals tsa_forward with k_keep = the count the budget found (batch entry by batch entry).
+ *   k_max: capacity, 1..L (k_max = L never clamps; a smaller k_max keeps the k_max best tokens when the
+ *          budget asks for more)
+ *   O [B,Hq,L,d] bf16 out or NULL;  residual as in tsa_decompress or NULL
+ *   k_keep_out [B] int32, device, out or NULL: the counts used
+ *   idx_out [B,Hs,k_max] int32, device, out or NULL: row (b, h) holds k_keep_out[b] indices, the rest
+ *          of the row is unspecified
+ *   ws: tsa_forward_dynamic_workspace_bytes(desc, k_max) bytes */
+size_t tsa_forward_dynamic_workspace_bytes(const tsa_desc* desc, int32_t k_max);
+int tsa_forward_dynamic(const tsa_desc* desc, const void* Q, const void* K, const void* V, double tau_cov, int32_t k_max,
+                        void* O, void* residual, int32_t* k_keep_out, int32_t* idx_out,
+                        void* ws, size_t ws_bytes, void* stream);
+
 /* Sparse layer selection (Section 2.4).  Offline preprocessing in the paper; here as kernels on
  * caller-supplied hidden states.
  *

@@ -17,6 +17,7 @@ TSA_OK, TSA_ERR_ARG, TSA_ERR_UNSUPPORTED, TSA_ERR_WORKSPACE, TSA_ERR_HIP = 0, 1,
 EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_bytes", "tsa_score", "tsa_coverage_budget",
            "tsa_score_queries", "tsa_gather_queries", "tsa_pool_queries_workspace_bytes", "tsa_pool_queries",
            "tsa_select", "tsa_compress", "tsa_attend_workspace_bytes", "tsa_attend", "tsa_decompress", "tsa_compress_v_tiles", "tsa_attend_fused", "tsa_forward",
+           "tsa_forward_dynamic_workspace_bytes", "tsa_forward_dynamic",
            "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe")
 
 
@@ -92,6 +93,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_attend_workspace_bytes.argtypes = [dp, i32, i32]
     lib.tsa_decompress.restype = ctypes.c_int
     lib.tsa_decompress.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp]
+    lib.tsa_forward_dynamic_workspace_bytes.restype = sz
+    lib.tsa_forward_dynamic_workspace_bytes.argtypes = [dp, i32]
+    lib.tsa_forward_dynamic.restype = ctypes.c_int
+    lib.tsa_forward_dynamic.argtypes = [dp, vp, vp, vp, ctypes.c_double, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.tsa_forward.restype = ctypes.c_int
     lib.tsa_forward.argtypes = [dp, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.tsa_layer_drift_workspace_bytes.restype = sz
@@ -217,6 +222,20 @@ def tsa_attend_fused(desc, Q, K, Vt, idx, inv, k_keep, O=None, Oc=None, residual
     _check(load_library().tsa_attend_fused(ctypes.byref(desc), _ptr(Q), _ptr(K), _ptr(Vt), _ptr(idx), _ptr(inv), k_keep,
                                            _ptr(block_list), block_size, max_blocks_per_row, _ptr(O), _ptr(Oc),
                                            _ptr(residual), _stream()))
+
+
+def alloc_forward_dynamic_workspace(desc, k_max, device="cuda"):
+    """Device buffer of tsa_forward_dynamic_workspace_bytes() bytes."""
+    n = load_library().tsa_forward_dynamic_workspace_bytes(ctypes.byref(desc), k_max)
+    if n == 0:
+        raise TsaError(TSA_ERR_ARG, tsa_last_error())
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def tsa_forward_dynamic(desc, Q, K, V, tau_cov, k_max, O, ws, residual=None, k_keep_out=None, idx_out=None):
+    p, n = _ws(ws)
+    _check(load_library().tsa_forward_dynamic(ctypes.byref(desc), _ptr(Q), _ptr(K), _ptr(V), float(tau_cov), k_max,
+                                              _ptr(O), _ptr(residual), _ptr(k_keep_out), _ptr(idx_out), p, n, _stream()))
 
 
 def tsa_forward(desc, Q, K, V, k_keep, O, ws, residual=None, idx_out=None,

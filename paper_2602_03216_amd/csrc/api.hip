@@ -87,6 +87,7 @@ int check_block_list(const int32_t* bl, int32_t block_size, int32_t max_blocks) 
 // Carving of the workspace used by tsa_forward (every piece 256-byte aligned).
 struct ForwardWs {
   size_t scores, score_ws, select_ws, idx, inv, Vt, total;
+  size_t budget_ws, k_dev, total_dynamic;    // tsa_forward_dynamic: the budget's scratch and the counts it writes
 };
 
 ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
@@ -102,6 +103,9 @@ ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
   w.inv = take(Hs * dm.L * sizeof(int32_t));
   w.Vt = take(tsa::v_tiles_bytes(dm.B, dm.group_mode ? dm.Hkv : dm.Hq, k, dm.d));
   w.total = off > tsa::budget_ws_bytes(dm) ? off : tsa::budget_ws_bytes(dm);
+  w.budget_ws = take(tsa::budget_ws_bytes(dm));
+  w.k_dev = take((size_t)dm.B * sizeof(int32_t));
+  w.total_dynamic = off;
   return w;
 }
 
@@ -109,7 +113,7 @@ ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
 
 extern "C" {
 
-int tsa_version(void) { return 5; }
+int tsa_version(void) { return 6; }
 
 const char* tsa_last_error(void) { return g_err; }
 
@@ -331,6 +335,51 @@ int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* 
     const size_t Hs = (size_t)dm.B * (dm.group_mode ? dm.Hkv : dm.Hq);
     if ((rc = hip_status(hipMemcpyAsync(idx_out, idx, Hs * k_keep * sizeof(int32_t), hipMemcpyDeviceToDevice, st),
                          "tsa_forward(idx copy)"))) return rc;
+  }
+  return TSA_OK;
+}
+
+size_t tsa_forward_dynamic_workspace_bytes(const tsa_desc* desc, int32_t k_max) {
+  tsa::Dims dm;
+  if (check_desc(desc, &dm) || check_k(dm, k_max)) return 0;
+  return forward_layout(dm, k_max).total_dynamic;
+}
+
+int tsa_forward_dynamic(const tsa_desc* desc, const void* Q, const void* K, const void* V, double tau_cov, int32_t k_max,
+                        void* O, void* residual, int32_t* k_keep_out, int32_t* idx_out,
+                        void* ws, size_t ws_bytes, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_max))) return rc;
+  if (!(tau_cov >= 0.0) || !(tau_cov <= 1.0)) return fail(TSA_ERR_ARG, "tau_cov must lie in [0, 1]");
+  if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(V, "V"))) return rc;
+  if (!O && !residual) return fail(TSA_ERR_ARG, "both O and residual are NULL");
+  if ((rc = check_ptr(O, "O", true)) || (rc = check_ptr(residual, "residual", true)) || (rc = check_ptr(idx_out, "idx_out", true)))
+    return rc;
+  if (k_keep_out && ((uintptr_t)k_keep_out & 3)) return fail(TSA_ERR_ARG, "k_keep_out is not 4-byte aligned");
+  const ForwardWs w = forward_layout(dm, k_max);
+  if ((rc = check_ws(ws, ws_bytes, w.total_dynamic))) return rc;
+  char* base = (char*)ws;
+  float* scores = (float*)(base + w.scores);
+  int32_t* idx = (int32_t*)(base + w.idx);
+  int32_t* inv = (int32_t*)(base + w.inv);
+  int32_t* k_dev = (int32_t*)(base + w.k_dev);
+  void* Vt = base + w.Vt;
+  hipStream_t st = (hipStream_t)stream;
+  // Algorithm 1 in its own order: scores, budget from the cross-head mass, selection with that budget;
+  // every later launch is sized for k_max and reads the count of its batch entry from k_dev.
+  if ((rc = hip_status(tsa::launch_score(dm, Q, K, scores, base + w.score_ws, st), "tsa_forward_dynamic(score)"))) return rc;
+  if ((rc = hip_status(tsa::launch_budget(dm, scores, tau_cov, k_dev, base + w.budget_ws, st, k_max), "tsa_forward_dynamic(budget)"))) return rc;
+  if ((rc = hip_status(tsa::launch_select(dm, scores, k_max, idx, inv, base + w.select_ws, st, k_dev), "tsa_forward_dynamic(select)"))) return rc;
+  if ((rc = hip_status(tsa::launch_compress_tiled(dm, Q, K, V, idx, k_max, nullptr, nullptr, Vt, st, k_dev), "tsa_forward_dynamic(V tiles)"))) return rc;
+  if ((rc = hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_max, nullptr, 0, 0, nullptr, O, residual, st, k_dev),
+                       "tsa_forward_dynamic(attend)"))) return rc;
+  if (k_keep_out && (rc = hip_status(hipMemcpyAsync(k_keep_out, k_dev, (size_t)dm.B * sizeof(int32_t), hipMemcpyDeviceToDevice, st),
+                                     "tsa_forward_dynamic(count copy)"))) return rc;
+  if (idx_out) {
+    const size_t Hs = (size_t)dm.B * (dm.group_mode ? dm.Hkv : dm.Hq);
+    if ((rc = hip_status(hipMemcpyAsync(idx_out, idx, Hs * k_max * sizeof(int32_t), hipMemcpyDeviceToDevice, st),
+                         "tsa_forward_dynamic(idx copy)"))) return rc;
   }
   return TSA_OK;
 }

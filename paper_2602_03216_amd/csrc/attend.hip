@@ -64,6 +64,7 @@ struct AttendArgs {
   int block;                   // block size of the list: 64, 128 or 256 tokens
   int exact;                   // 1: scores scaled in fp32 (host side only: selects the kernel)
   int BH, Hq, kvh, Lc, nq_tiles, nk_tiles;
+  const int32_t* k_dev;        // fused form: compacted rows per batch entry, decided on the device (NULL: Lc)
   float c;                     // scale * log2(e)
   // Fused form (gather in the loads, scatter in the epilogue): Q and K are the ORIGINAL tensors of
   // L tokens (K with Hkv heads), compacted row r of selection row `sel` is token idx[sel][r];
@@ -334,15 +335,24 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const int heads_per_xcd = (a.BH + 7) >> 3;
   const int hp = (slot % heads_per_xcd) * 8 + xcd;
   if (hp >= a.BH) return;
-  const int qt = a.nq_tiles - 1 - slot / heads_per_xcd;
   const int b = hp / a.Hq, hr = hp % a.Hq;
+  // Rows of this batch entry's compacted set: the launch's count, or (fused form with a coverage
+  // budget decided on the device) the count read from k_dev; a.Lc stays the capacity, i.e. the row
+  // stride of idx and of the tile arrays, and the grid is sized for it.
+  int Lc = a.Lc, nq_tiles = a.nq_tiles;
+  if (FUSED && a.k_dev) {
+    Lc = a.k_dev[b];
+    nq_tiles = (Lc + BM - 1) / BM;
+  }
+  const int qt = nq_tiles - 1 - slot / heads_per_xcd;
+  if (qt < 0) return;
   const int g = a.Hq / a.kvh;
   const int n_grp = FUSED ? a.Hkv : a.kvh, g_grp = a.Hq / n_grp;
   const int h = (hr % n_grp) * g_grp + hr / n_grp;       // heads of one KV group are 8 apart in hp
   const long long bh = (long long)b * a.Hq + h;
   const long long bkv = (long long)b * a.kvh + h / g;    // head of K^ / V^ (fused: of the index set and the V tiles)
   // rows of Q and K: the compacted tensors, or (fused) the original ones addressed through idx
-  const int n_rows = FUSED ? a.L : a.Lc;
+  const int n_rows = FUSED ? a.L : Lc;
   const long long head_bytes = (long long)n_rows * ROWB;
   const long long k_head = FUSED ? (long long)b * a.Hkv + h / g_grp : bkv;
 
@@ -353,7 +363,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const int32_t* idx_row = FUSED ? a.idx + bkv * a.Lc : nullptr;
   // index loads past the end of the set return 0 (token 0): such rows are only ever read as keys
   // beyond every query of the workgroup, which causality masks
-  const __amdgpu_buffer_rsrc_t Ir = __builtin_amdgcn_make_buffer_rsrc((void*)idx_row, 0, FUSED ? a.Lc * 4 : 0, 0x00020000);
+  const __amdgpu_buffer_rsrc_t Ir = __builtin_amdgcn_make_buffer_rsrc((void*)idx_row, 0, FUSED ? Lc * 4 : 0, 0x00020000);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int q0 = qt * BM;
@@ -379,7 +389,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   if (zfill) {
     inv_row = a.inv + bkv * a.L;
     const int tok_lo = qt == 0 ? 0 : idx_row[q0];
-    z_hi = q0 + BM >= a.Lc ? a.L : idx_row[q0 + BM];
+    z_hi = q0 + BM >= Lc ? a.L : idx_row[q0 + BM];
     zrow = (u32x4*)(a.Of + bh * a.L * D) + (tid % LPR);
     zt = tok_lo + tid / LPR;
     zr = zt < z_hi ? inv_row[zt] : 0;
@@ -398,7 +408,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     int qrow_off = (wrow0 + 32 * qs + lo) * ROWB;
     if (FUSED) {
       const int qr = wrow0 + 32 * qs + lo;
-      qrow_off = qr < a.Lc ? idx_row[qr] * ROWB : a.L * ROWB;   // past the end: out of the buffer's range, reads zeros
+      qrow_off = qr < Lc ? idx_row[qr] * ROWB : a.L * ROWB;   // past the end: out of the buffer's range, reads zeros
     }
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
@@ -423,7 +433,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   TileGen gen;
   gen.plain = a.block_list == nullptr;
   gen.plain_i = 0;
-  gen.plain_n = (min(q0 + BM, a.Lc) + BN - 1) / BN;
+  gen.plain_n = (min(q0 + BM, Lc) + BN - 1) / BN;
   gen.sub = gen.kb = gen.use = 0;
   gen.n_lists = 1;
   gen.block = BM;
@@ -437,7 +447,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     gen.n_lists = BM / a.block;
     gen.tiles_per_block = a.block / BN;
     gen.full = 0;
-    const int nqb = (a.Lc + a.block - 1) / a.block;
+    const int nqb = (Lc + a.block - 1) / a.block;
     const int32_t* bl = a.block_list + bh * a.bl_head_stride;
 #pragma unroll
     for (int j = 0; j < kMaxLists; ++j) {
@@ -776,7 +786,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     const int qrow = wrow0 + 32 * qs + lo;
     const float lt = l[qs] + __shfl_xor(l[qs], 32);
     const float inv_l = lt > 0.f ? 1.0f / lt : 0.f;
-    if (qrow < a.Lc) {
+    if (qrow < Lc) {
       __bf16* orow = a.O ? a.O + (bh * a.Lc + qrow) * D : nullptr;
       __bf16* frow = nullptr;                       // fused: the token's row of the full-length output
       __bf16* xrow = nullptr;                       // fused: the token's slice of the residual stream
@@ -837,13 +847,16 @@ hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale
   a.BH = B * Hq; a.Hq = Hq; a.kvh = kv_heads; a.Lc = Lc;
   a.c = scale * kLog2e;
   a.idx = nullptr; a.inv = nullptr; a.Of = nullptr; a.X = nullptr; a.L = Lc; a.Hkv = kv_heads;
+  a.k_dev = nullptr;
   return launch_any<false>(a, d, st);
 }
 
 hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, const void* Vt, const int32_t* idx,
                                const int32_t* inv, int k_keep, const int32_t* block_list, int block_size,
-                               int max_blocks_per_row, void* Oc, void* O, void* residual, hipStream_t st) {
+                               int max_blocks_per_row, void* Oc, void* O, void* residual, hipStream_t st,
+                               const int32_t* k_dev) {
   AttendArgs a;
+  a.k_dev = k_dev;
   a.exact = dm.exact_scale;
   a.block = block_list ? block_size : BM;
   a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;

@@ -41,6 +41,7 @@ struct BudArgs {
   int32_t* k_keep;       // [B]
   int Hq, L;
   double tau;
+  int k_max;             // upper bound of the result (capacity of the caller's buffers)
 };
 
 __device__ __forceinline__ uint32_t order_key(float f) {
@@ -190,6 +191,7 @@ __global__ void bud_final_kernel(BudArgs a) {
     }
     long long keep = (long long)a.L - k_sparse;
     if (keep < 1) keep = 1;
+    if (keep > a.k_max) keep = a.k_max;
     a.k_keep[b] = (int32_t)keep;
   }
 }
@@ -202,8 +204,10 @@ size_t budget_ws_bytes(const Dims& dm) {
   return align256((size_t)dm.B * sizeof(BudRow)) + align256((size_t)dm.B * dm.L * sizeof(float));
 }
 
-hipError_t launch_budget(const Dims& dm, const float* scores, double tau_cov, int32_t* k_keep, void* ws, hipStream_t st) {
+hipError_t launch_budget(const Dims& dm, const float* scores, double tau_cov, int32_t* k_keep, void* ws, hipStream_t st,
+                         int k_max) {
   BudArgs a;
+  a.k_max = k_max > 0 ? k_max : dm.L;
   a.scores = scores;
   a.rows = (BudRow*)ws;
   a.sl = (float*)((char*)ws + align256((size_t)dm.B * sizeof(BudRow)));

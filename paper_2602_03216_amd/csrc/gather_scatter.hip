@@ -208,6 +208,8 @@ struct CompressTiledArgs {
   const u32x4* Q; const u32x4* K; const u32x4* V; const int32_t* idx;
   u32x4* Qc; u32x4* Kc; __bf16* Vt;
   int Hq, Hkv, L, k, group_mode, nk_tiles;
+  const int32_t* k_dev;       // count per batch entry decided on the device (NULL: k); rows of idx and the tile
+                              // arrays keep the stride of k
 };
 
 template <int D>
@@ -225,7 +227,9 @@ __global__ __launch_bounds__(kThreads) void compress_tiled_kernel(CompressTiledA
   const bool kv_owner = a.group_mode == 0 || h % g == 0;
   if (!a.Qc && !kv_owner) return;            // nothing to do; the same for every thread of the workgroup
   const int r0 = t * kKeyTile;
-  if (threadIdx.x < kKeyTile) tok[threadIdx.x] = r0 + (int)threadIdx.x < a.k ? a.idx[sel_head * a.k + r0 + threadIdx.x] : -1;
+  const int k_here = a.k_dev ? a.k_dev[b] : a.k;
+  if (r0 >= k_here) return;                  // tiles past this batch entry's count; the same for every thread
+  if (threadIdx.x < kKeyTile) tok[threadIdx.x] = r0 + (int)threadIdx.x < k_here ? a.idx[sel_head * a.k + r0 + threadIdx.x] : -1;
   __syncthreads();
 #pragma unroll
   for (int c = threadIdx.x; c < kKeyTile * LPR; c += kThreads) {
@@ -273,8 +277,9 @@ hipError_t launch_v_tiles(int B, int kv_heads, int Lc, int d, const void* V, voi
 }
 
 hipError_t launch_compress_tiled(const Dims& dm, const void* Q, const void* K, const void* V, const int32_t* idx,
-                                 int k_keep, void* Qc, void* Kc, void* Vt, hipStream_t st) {
+                                 int k_keep, void* Qc, void* Kc, void* Vt, hipStream_t st, const int32_t* k_dev) {
   CompressTiledArgs a;
+  a.k_dev = k_dev;
   a.Q = (const u32x4*)Q; a.K = (const u32x4*)K; a.V = (const u32x4*)V; a.idx = idx;
   a.Qc = (u32x4*)Qc; a.Kc = (u32x4*)Kc; a.Vt = (__bf16*)Vt;
   a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.L = dm.L; a.k = k_keep; a.group_mode = dm.group_mode;

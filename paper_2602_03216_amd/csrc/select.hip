@@ -43,6 +43,13 @@ struct SelArgs {
   uint2* counts;              // [row][nslices][kWaves] (n_gt, n_eq)
   int L, k, ff, fl, nslices;
   int slice;                  // tokens per workgroup; a wavefront owns slice / kWaves contiguous tokens
+  // Count decided on the device (dynamic coverage budget): k_dev[b] replaces k for the rows of batch
+  // entry b (NULL: every row takes k); a row of idx is k_stride entries long either way.
+  const int32_t* k_dev;
+  int k_stride, rows_per_b;
+  __device__ __forceinline__ uint32_t k_of(long long row) const {
+    return (uint32_t)(k_dev ? k_dev[row / rows_per_b] : k);
+  }
 };
 
 // fp32 -> uint32 with the same order (-0 and +0 map to the same key)
@@ -103,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void hist_kernel(SelArgs a) {
 
   if (wave == 0) {
     SelState st;
-    if (PASS == 0) { st.prefix = 0u; st.krem = (uint32_t)a.k; }
+    if (PASS == 0) { st.prefix = 0u; st.krem = a.k_of(row); }
     else st = next_state(rw->hist[PASS - 1], rw->state[PASS - 1], shift + 8, lane);
     if (lane == 0) {
       sh_state = st;
@@ -181,7 +188,7 @@ __global__ __launch_bounds__(kThreads) void write_kernel(SelArgs a) {
   const long long row = blockIdx.y;
   const RowWs* rw = a.rows + row;
   const float* s = a.scores + row * a.L;
-  int32_t* out_idx = a.idx + row * a.k;
+  int32_t* out_idx = a.idx + row * a.k_stride;
   int32_t* out_inv = a.inv ? a.inv + row * a.L : nullptr;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const uint32_t T = rw->state[4].prefix;
@@ -240,13 +247,13 @@ __global__ __launch_bounds__(kThreads) void select_small_kernel(SelArgs a) {
   __shared__ uint2 cnt[kWaves];
   const long long row = blockIdx.x;
   const float* s = a.scores + row * a.L;
-  int32_t* out_idx = a.idx + row * a.k;
+  int32_t* out_idx = a.idx + row * a.k_stride;
   int32_t* out_inv = a.inv ? a.inv + row * a.L : nullptr;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   for (int t = tid; t < a.L; t += kThreads) keys[t] = key_at(s, t, a.L, a.ff, a.fl);
   SelState st;
   st.prefix = 0u;
-  st.krem = (uint32_t)a.k;
+  st.krem = a.k_of(row);
 #pragma unroll 1
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
@@ -356,7 +363,7 @@ size_t select_ws_bytes(const Dims& dm) {
 }
 
 hipError_t launch_select(const Dims& dm, const float* scores, int k_keep, int32_t* idx, int32_t* inv,
-                         void* ws, hipStream_t st) {
+                         void* ws, hipStream_t st, const int32_t* k_dev) {
   const int rows = n_rows(dm);
   SelArgs a;
   a.rows = (RowWs*)ws;
@@ -370,6 +377,7 @@ hipError_t launch_select(const Dims& dm, const float* scores, int k_keep, int32_
   }
   a.idx = idx; a.inv = inv;
   a.L = dm.L; a.k = k_keep; a.ff = dm.force_first; a.fl = dm.force_last; a.nslices = n_slices(dm);
+  a.k_dev = k_dev; a.k_stride = k_keep; a.rows_per_b = rows / dm.B;
   a.slice = slice_for(dm);
   if (dm.L <= kSmallL) {
     const size_t lds = ((size_t)dm.L + kWaves * 256) * sizeof(uint32_t);

@@ -51,12 +51,16 @@ hipError_t launch_pool_queries(const Dims& dm, const void* Q, int n_pool, void* 
 
 // select.hip
 size_t select_ws_bytes(const Dims& dm);
+// k_dev (device, [B], may be NULL): the count of every batch entry as decided on the device; k_keep is
+// then the capacity (row stride of idx), and entries of idx past a row's count are left untouched.
 hipError_t launch_select(const Dims& dm, const float* scores, int k_keep, int32_t* idx, int32_t* inv,
-                         void* ws, hipStream_t st);
+                         void* ws, hipStream_t st, const int32_t* k_dev = nullptr);
 
 // budget.hip
 size_t budget_ws_bytes(const Dims& dm);
-hipError_t launch_budget(const Dims& dm, const float* scores, double tau_cov, int32_t* k_keep, void* ws, hipStream_t st);
+// k_max > 0: the result is clamped to it (the capacity of the buffers that will hold the selection)
+hipError_t launch_budget(const Dims& dm, const float* scores, double tau_cov, int32_t* k_keep, void* ws, hipStream_t st,
+                         int k_max = 0);
 
 // drift.hip
 size_t drift_ws_bytes(long long n_tokens);
@@ -82,7 +86,7 @@ inline size_t v_tiles_bytes(int B, int kv_heads, int Lc, int d) {
 // Qc, Kc row-major and V directly as tiled V^T (the form tsa_forward uses).
 hipError_t launch_v_tiles(int B, int kv_heads, int Lc, int d, const void* V, void* Vt, hipStream_t st);
 hipError_t launch_compress_tiled(const Dims& dm, const void* Q, const void* K, const void* V, const int32_t* idx,
-                                 int k_keep, void* Qc, void* Kc, void* Vt, hipStream_t st);
+                                 int k_keep, void* Qc, void* Kc, void* Vt, hipStream_t st, const int32_t* k_dev = nullptr);
 
 // attend.hip
 hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
@@ -96,7 +100,8 @@ hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale
 // (may be NULL) gets the output rows added in place.
 hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, const void* Vt, const int32_t* idx,
                                const int32_t* inv, int k_keep, const int32_t* block_list, int block_size,
-                               int max_blocks_per_row, void* Oc, void* O, void* residual, hipStream_t st);
+                               int max_blocks_per_row, void* Oc, void* O, void* residual, hipStream_t st,
+                               const int32_t* k_dev = nullptr);
 
 // probe.hip: bare MFMA loop, 8 * iters MFMAs per wavefront, 4 wavefronts per workgroup
 hipError_t launch_mfma_probe(const void* operands, int iters, int blocks, float* sink, long long* clocks, hipStream_t st);

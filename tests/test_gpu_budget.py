@@ -80,3 +80,82 @@ def test_budget_on_scored_workload_then_forward(tsa):
         assert torch.all(idx[0, :, :4] == torch.arange(4, device=gu.DEV, dtype=torch.int32))
         nonzero_rows = (O[0].float().abs().sum(-1) > 0).sum(-1)
         assert torch.all(nonzero_rows <= k) and torch.all(nonzero_rows >= k - 2)
+
+
+def _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed):
+    """tsa_forward_dynamic against (a) the oracle's budget on the library's own scores: the count is an
+    integer decided by fp64 masses of the same fp32 numbers, so it must match exactly; (b) tsa_forward
+    with that count, batch entry by batch entry: the same kernels on the same data, bit for bit."""
+    r = np.random.Generator(np.random.PCG64(seed))
+    Lq = min(64, L)
+    Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, L, d)), gu.rand_bits(r, (B, Hkv, L, d), 1.5), gu.rand_bits(r, (B, Hkv, L, d))
+    Q, K, V = gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb)
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq, group_mode=group_mode)
+    Hs = Hkv if group_mode else Hq
+    s = torch.empty((B, Hq, L), dtype=torch.float32, device=gu.DEV)
+    tsa.tsa_score(desc, Q, K, s, tsa.alloc_workspace(desc, 1, gu.DEV))
+    want_k = np.minimum(orc.coverage_budget(s.cpu().numpy(), tau_cov), k_max)
+    O = torch.full((B, Hq, L, d), 7.0, dtype=torch.bfloat16, device=gu.DEV)
+    kk = torch.full((B,), -3, dtype=torch.int32, device=gu.DEV)
+    idx = torch.full((B, Hs, k_max), -9, dtype=torch.int32, device=gu.DEV)
+    tsa.tsa_forward_dynamic(desc, Q, K, V, tau_cov, k_max, O, tsa.alloc_forward_dynamic_workspace(desc, k_max, gu.DEV),
+                            k_keep_out=kk, idx_out=idx)
+    torch.cuda.synchronize()
+    got_k = kk.cpu().numpy()
+    assert np.array_equal(got_k, want_k), (got_k, want_k)
+    for b in range(B):
+        k = int(got_k[b])
+        d1 = tsa.make_desc(1, Hq, Hkv, L, d, Lq, group_mode=group_mode)
+        O1 = torch.empty((1, Hq, L, d), dtype=torch.bfloat16, device=gu.DEV)
+        i1 = torch.empty((1, Hs, k), dtype=torch.int32, device=gu.DEV)
+        tsa.tsa_forward(d1, Q[b:b + 1].contiguous(), K[b:b + 1].contiguous(), V[b:b + 1].contiguous(), k, O1,
+                        tsa.alloc_workspace(d1, k, gu.DEV), idx_out=i1)
+        torch.cuda.synchronize()
+        assert torch.equal(idx[b, :, :k], i1[0]), "index sets of batch entry %d" % b
+        assert torch.equal(O[b], O1[0]), "output of batch entry %d" % b
+    return got_k
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,L,d,tau_cov,k_max,group_mode", [
+    (1, 4, 2, 3000, 128, 0.02, 3000, 0),
+    (3, 4, 4, 1700, 64, 0.05, 1700, 0),        # three batch entries, three different counts
+    (2, 6, 2, 2500, 128, 0.01, 2500, 1),
+    (2, 4, 2, 2048, 128, 0.3, 600, 0),         # the budget asks for more than k_max: clamped
+    (1, 2, 2, 700, 128, 0.0, 700, 0),          # tau_cov = 0: nothing is dropped
+    (1, 2, 1, 900, 64, 1.0, 900, 0),           # tau_cov = 1: a single token is kept
+])
+def test_forward_dynamic_equals_budget_then_forward(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode):
+    got = _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed=4100 + L)
+    print("tau_cov %.3g: k_keep %s of %d (k_max %d)" % (tau_cov, got.tolist(), L, k_max))
+
+
+def test_forward_dynamic_against_the_oracle(tsa):
+    """The oracle end to end: its own scores, its own budget, its own forward with that count.  The
+    margin of the count is checked first (the cumulative mass must not cross tau_cov within the
+    library's score error of 3e-5), then index sets bit-exact and outputs within the bars."""
+    inp = gen.make_inputs(3, L=4096)
+    cfg = inp.cfg
+    B, Hq, Hkv, L, d, Lq = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"]
+    s_ref = orc.score(orc.bf16_to_f64(inp.Q), orc.bf16_to_f64(inp.K), Lq)
+    tau_cov = 0.01
+    k_lo, k_hi = orc.coverage_budget(s_ref, tau_cov * (1 - 1e-3))[0], orc.coverage_budget(s_ref, tau_cov * (1 + 1e-3))[0]
+    k = int(orc.coverage_budget(s_ref, tau_cov)[0])
+    from tests.margin import enforce_margin
+    enforce_margin(inp, [k], 0)
+    s_ref = orc.score(orc.bf16_to_f64(inp.Q), orc.bf16_to_f64(inp.K), Lq)
+    k = int(orc.coverage_budget(s_ref, tau_cov)[0])
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq)
+    Q, K, V = gu.to_dev(inp.Q), gu.to_dev(inp.K), gu.to_dev(inp.V)
+    O = torch.empty((B, Hq, L, d), dtype=torch.bfloat16, device=gu.DEV)
+    kk = torch.zeros((B,), dtype=torch.int32, device=gu.DEV)
+    idx = torch.zeros((B, Hq, L), dtype=torch.int32, device=gu.DEV)
+    tsa.tsa_forward_dynamic(desc, Q, K, V, tau_cov, L, O, tsa.alloc_forward_dynamic_workspace(desc, L, gu.DEV),
+                            k_keep_out=kk, idx_out=idx)
+    torch.cuda.synchronize()
+    got_k = int(kk[0].item())
+    assert k_hi <= got_k <= k_lo, (k_hi, got_k, k_lo)
+    if got_k != k:
+        pytest.skip("the count sits on a rounding boundary of the scores (%d vs %d)" % (got_k, k))
+    ref = orc.forward(inp.Q, inp.K, inp.V, k, Lq)
+    assert np.array_equal(idx[:, :, :k].cpu().numpy(), ref["idx"])
+    gu.assert_output_close(gu.from_dev(O), ref["O"], "forward_dynamic")
