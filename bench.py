@@ -145,9 +145,37 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
         }
         for nm in ("score", "select", "compress", "decompress"):
             rec[nm + "_frac_hbm_peak"] = rec[nm + "_gbs"] / HBM_PEAK_GBS
+        if tau == taus[0]:
+            rec["dynamic_coverage"] = bench_dynamic(tsa, torch, desc, Q, K, V, O, scores, kk, ws, k, steps, warmup, t_fwd)
         out["per_tau"][str(tau)] = rec
         del ws, scores, idx, inv, Qc, Kc, Vc, Oc, vt
     return out, inp
+
+
+def bench_dynamic(tsa, torch, desc, Q, K, V, O, scores, kk, ws, k_target, steps, warmup, t_static):
+    """The layer with the coverage budget decided on the device (tsa_forward_dynamic, capacity k_max = L),
+    at the mass threshold that makes the budget keep about as many tokens as the fixed ratio does, so the
+    two forms of the layer can be compared at the same amount of work.  (On these synthetic scores that
+    threshold is far above the paper's 0.005: the attention of random keys is nearly uniform.)"""
+    lo, hi = 0.0, 1.0
+    for _ in range(30):                      # k_keep falls as tau_cov grows: bisection on the device budget
+        mid = 0.5 * (lo + hi)
+        tsa.tsa_coverage_budget(desc, scores, mid, kk, ws)
+        if int(kk[0].item()) > k_target:
+            lo = mid
+        else:
+            hi = mid
+    tau_cov = hi
+    L = desc.L
+    wsd = tsa.alloc_forward_dynamic_workspace(desc, L, "cuda:0")
+    kout = torch.zeros(desc.B, dtype=torch.int32, device="cuda:0")
+    fwd = lambda: tsa.tsa_forward_dynamic(desc, Q, K, V, tau_cov, L, O, wsd, k_keep_out=kout)
+    for _ in range(warmup):
+        fwd()
+    torch.cuda.synchronize()
+    t = _events_ms(fwd, steps, torch)
+    return {"tau_cov": tau_cov, "k_max": L, "k_keep_found": int(kout[0].item()), "k_keep_fixed_ratio": k_target,
+            "forward_dynamic_ms": t, "forward_fixed_ms": t_static}
 
 
 def bench_stack(tsa, torch, gen, steps, warmup):
