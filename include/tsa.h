@@ -229,9 +229,14 @@ int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* 
  *   k_keep_out [B] int32, device, out or NULL: the counts used
  *   idx_out [B,Hs,k_max] int32, device, out or NULL: row (b, h) holds k_keep_out[b] indices, the rest
  *          of the row is unspecified
+ *   block_list / block_size / max_blocks_per_row as in tsa_attend, laid out for k_max compacted rows
+ *          ([ceil(k_max/block_size), max_blocks_per_row], per (b, h) if the descriptor says so): a batch
+ *          entry that keeps fewer rows uses the first ceil(k_keep/block_size) rows of its table, so
+ *          the pattern must not depend on the total (sink + window and vertical + slash lists do not)
  *   ws: tsa_forward_dynamic_workspace_bytes(desc, k_max) bytes */
 size_t tsa_forward_dynamic_workspace_bytes(const tsa_desc* desc, int32_t k_max);
 int tsa_forward_dynamic(const tsa_desc* desc, const void* Q, const void* K, const void* V, double tau_cov, int32_t k_max,
+                        const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
                         void* O, void* residual, int32_t* k_keep_out, int32_t* idx_out,
                         void* ws, size_t ws_bytes, void* stream);
 

@@ -96,7 +96,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_forward_dynamic_workspace_bytes.restype = sz
     lib.tsa_forward_dynamic_workspace_bytes.argtypes = [dp, i32]
     lib.tsa_forward_dynamic.restype = ctypes.c_int
-    lib.tsa_forward_dynamic.argtypes = [dp, vp, vp, vp, ctypes.c_double, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.tsa_forward_dynamic.argtypes = [dp, vp, vp, vp, ctypes.c_double, i32, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.tsa_forward.restype = ctypes.c_int
     lib.tsa_forward.argtypes = [dp, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, sz, vp]
     lib.tsa_layer_drift_workspace_bytes.restype = sz
@@ -232,9 +232,11 @@ def alloc_forward_dynamic_workspace(desc, k_max, device="cuda"):
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
-def tsa_forward_dynamic(desc, Q, K, V, tau_cov, k_max, O, ws, residual=None, k_keep_out=None, idx_out=None):
+def tsa_forward_dynamic(desc, Q, K, V, tau_cov, k_max, O, ws, residual=None, k_keep_out=None, idx_out=None,
+                        block_list=None, block_size=0, max_blocks_per_row=0):
     p, n = _ws(ws)
     _check(load_library().tsa_forward_dynamic(ctypes.byref(desc), _ptr(Q), _ptr(K), _ptr(V), float(tau_cov), k_max,
+                                              _ptr(block_list), block_size, max_blocks_per_row,
                                               _ptr(O), _ptr(residual), _ptr(k_keep_out), _ptr(idx_out), p, n, _stream()))
 
 

@@ -346,6 +346,7 @@ size_t tsa_forward_dynamic_workspace_bytes(const tsa_desc* desc, int32_t k_max) 
 }
 
 int tsa_forward_dynamic(const tsa_desc* desc, const void* Q, const void* K, const void* V, double tau_cov, int32_t k_max,
+                        const int32_t* block_list, int32_t block_size, int32_t max_blocks_per_row,
                         void* O, void* residual, int32_t* k_keep_out, int32_t* idx_out,
                         void* ws, size_t ws_bytes, void* stream) {
   tsa::Dims dm;
@@ -357,6 +358,7 @@ int tsa_forward_dynamic(const tsa_desc* desc, const void* Q, const void* K, cons
   if ((rc = check_ptr(O, "O", true)) || (rc = check_ptr(residual, "residual", true)) || (rc = check_ptr(idx_out, "idx_out", true)))
     return rc;
   if (k_keep_out && ((uintptr_t)k_keep_out & 3)) return fail(TSA_ERR_ARG, "k_keep_out is not 4-byte aligned");
+  if ((rc = check_block_list(block_list, block_size, max_blocks_per_row))) return rc;
   const ForwardWs w = forward_layout(dm, k_max);
   if ((rc = check_ws(ws, ws_bytes, w.total_dynamic))) return rc;
   char* base = (char*)ws;
@@ -372,7 +374,8 @@ int tsa_forward_dynamic(const tsa_desc* desc, const void* Q, const void* K, cons
   if ((rc = hip_status(tsa::launch_budget(dm, scores, tau_cov, k_dev, base + w.budget_ws, st, k_max), "tsa_forward_dynamic(budget)"))) return rc;
   if ((rc = hip_status(tsa::launch_select(dm, scores, k_max, idx, inv, base + w.select_ws, st, k_dev), "tsa_forward_dynamic(select)"))) return rc;
   if ((rc = hip_status(tsa::launch_compress_tiled(dm, Q, K, V, idx, k_max, nullptr, nullptr, Vt, st, k_dev), "tsa_forward_dynamic(V tiles)"))) return rc;
-  if ((rc = hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_max, nullptr, 0, 0, nullptr, O, residual, st, k_dev),
+  if ((rc = hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_max, block_list, block_size, max_blocks_per_row,
+                                                nullptr, O, residual, st, k_dev),
                        "tsa_forward_dynamic(attend)"))) return rc;
   if (k_keep_out && (rc = hip_status(hipMemcpyAsync(k_keep_out, k_dev, (size_t)dm.B * sizeof(int32_t), hipMemcpyDeviceToDevice, st),
                                      "tsa_forward_dynamic(count copy)"))) return rc;

@@ -84,9 +84,9 @@ def test_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert lib.tsa_coverage_budget(dp, fake, 0.01, None, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_score(None, fake, fake, fake, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
     # the layer with the budget decided on the device
-    assert lib.tsa_forward_dynamic(dp, fake, fake, fake, 0.01, 0, fake, None, None, None, fake, 1 << 40, None) == tsa.TSA_ERR_ARG
-    assert lib.tsa_forward_dynamic(dp, fake, fake, fake, 1.5, 16, fake, None, None, None, fake, 1 << 40, None) == tsa.TSA_ERR_ARG
-    assert lib.tsa_forward_dynamic(dp, fake, fake, fake, 0.01, 16, None, None, None, None, fake, 1 << 40, None) == tsa.TSA_ERR_ARG
-    assert lib.tsa_forward_dynamic(dp, fake, fake, fake, 0.01, 16, fake, None, None, None, fake, 64, None) == tsa.TSA_ERR_WORKSPACE
+    assert lib.tsa_forward_dynamic(dp, fake, fake, fake, 0.01, 0, None, 0, 0, fake, None, None, None, fake, 1 << 40, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_forward_dynamic(dp, fake, fake, fake, 1.5, 16, None, 0, 0, fake, None, None, None, fake, 1 << 40, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_forward_dynamic(dp, fake, fake, fake, 0.01, 16, None, 0, 0, None, None, None, None, fake, 1 << 40, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_forward_dynamic(dp, fake, fake, fake, 0.01, 16, None, 0, 0, fake, None, None, None, fake, 64, None) == tsa.TSA_ERR_WORKSPACE
     assert lib.tsa_forward_dynamic_workspace_bytes(dp, 0) == 0
     assert lib.tsa_forward_dynamic_workspace_bytes(dp, 16) > lib.tsa_workspace_bytes(dp, 16)

@@ -82,7 +82,7 @@ def test_budget_on_scored_workload_then_forward(tsa):
         assert torch.all(nonzero_rows <= k) and torch.all(nonzero_rows >= k - 2)
 
 
-def _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed):
+def _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed, window=0):
     """tsa_forward_dynamic against (a) the oracle's budget on the library's own scores: the count is an
     integer decided by fp64 masses of the same fp32 numbers, so it must match exactly; (b) tsa_forward
     with that count, batch entry by batch entry: the same kernels on the same data, bit for bit."""
@@ -98,8 +98,12 @@ def _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed):
     O = torch.full((B, Hq, L, d), 7.0, dtype=torch.bfloat16, device=gu.DEV)
     kk = torch.full((B,), -3, dtype=torch.int32, device=gu.DEV)
     idx = torch.full((B, Hs, k_max), -9, dtype=torch.int32, device=gu.DEV)
+    kw = {}
+    if window:      # sink + window list laid out for k_max rows: a shorter set uses its first rows
+        bl = orc.lambda_block_list(k_max, 128, window, 1)
+        kw = dict(block_list=torch.from_numpy(bl).to(gu.DEV), block_size=128, max_blocks_per_row=bl.shape[1])
     tsa.tsa_forward_dynamic(desc, Q, K, V, tau_cov, k_max, O, tsa.alloc_forward_dynamic_workspace(desc, k_max, gu.DEV),
-                            k_keep_out=kk, idx_out=idx)
+                            k_keep_out=kk, idx_out=idx, **kw)
     torch.cuda.synchronize()
     got_k = kk.cpu().numpy()
     assert np.array_equal(got_k, want_k), (got_k, want_k)
@@ -109,7 +113,7 @@ def _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed):
         O1 = torch.empty((1, Hq, L, d), dtype=torch.bfloat16, device=gu.DEV)
         i1 = torch.empty((1, Hs, k), dtype=torch.int32, device=gu.DEV)
         tsa.tsa_forward(d1, Q[b:b + 1].contiguous(), K[b:b + 1].contiguous(), V[b:b + 1].contiguous(), k, O1,
-                        tsa.alloc_workspace(d1, k, gu.DEV), idx_out=i1)
+                        tsa.alloc_workspace(d1, k, gu.DEV), idx_out=i1, **kw)
         torch.cuda.synchronize()
         assert torch.equal(idx[b, :, :k], i1[0]), "index sets of batch entry %d" % b
         assert torch.equal(O[b], O1[0]), "output of batch entry %d" % b
@@ -118,6 +122,7 @@ def _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed):
 
 @pytest.mark.parametrize("B,Hq,Hkv,L,d,tau_cov,k_max,group_mode", [
     (1, 4, 2, 3000, 128, 0.02, 3000, 0),
+    (2, 4, 2, 3000, 128, 0.04, 3000, -512),    # with a sink + 512-token window block list (negative: window)
     (3, 4, 4, 1700, 64, 0.05, 1700, 0),        # three batch entries, three different counts
     (2, 6, 2, 2500, 128, 0.01, 2500, 1),
     (2, 4, 2, 2048, 128, 0.3, 600, 0),         # the budget asks for more than k_max: clamped
@@ -125,7 +130,8 @@ def _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed):
     (1, 2, 1, 900, 64, 1.0, 900, 0),           # tau_cov = 1: a single token is kept
 ])
 def test_forward_dynamic_equals_budget_then_forward(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode):
-    got = _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed=4100 + L)
+    window = -group_mode if group_mode < 0 else 0
+    got = _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, max(group_mode, 0), seed=4100 + L, window=window)
     print("tau_cov %.3g: k_keep %s of %d (k_max %d)" % (tau_cov, got.tolist(), L, k_max))
 
 
