@@ -31,13 +31,13 @@ class tsa_desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("L", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("last_q", ctypes.c_int32), ("pool_w", ctypes.c_int32),
                 ("group_mode", ctypes.c_int32), ("force_first", ctypes.c_int32), ("force_last", ctypes.c_int32),
-                ("scale", ctypes.c_float), ("block_list_per_head", ctypes.c_int32), ("exact_scale", ctypes.c_int32)]
+                ("scale", ctypes.c_float), ("block_list_per_head", ctypes.c_int32), ("fast_scale", ctypes.c_int32)]
 
 
 def make_desc(B, Hq, Hkv, L, d, last_q=64, pool_w=1, group_mode=0, force_first=0, force_last=0, scale=0.0,
-              block_list_per_head=0, exact_scale=0):
+              block_list_per_head=0, fast_scale=0):
     return tsa_desc(B, Hq, Hkv, L, d, last_q, pool_w, group_mode, force_first, force_last, scale, block_list_per_head,
-                    exact_scale)
+                    fast_scale)
 
 
 _lib = None

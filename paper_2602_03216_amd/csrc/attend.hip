@@ -21,12 +21,12 @@
 // The O rescale is lazy: the running max is only raised when a row's new max exceeds it by
 // more than 2^8, so most tiles skip the multiply over the whole accumulator; the final
 // division by the row sum makes the result independent of the max actually used.
-// The exponent s * scale * log2(e) - m costs no vector instruction in the pipelined loop: Q is
+// With tsa_desc.fast_scale the exponent s * scale * log2(e) - m costs no vector instruction in the pipelined loop: Q is
 // multiplied by scale * log2(e) once when it is loaded (and rounded back to bf16, one more rounding
 // of relative size 2^-9 on the query side), and the first MFMA of every QK chain starts from the
 // accumulator -m instead of 0, so the chain delivers s - m and the loop applies exp2 to it directly.
-// (Template flag SCALED_Q; tsa_desc.exact_scale selects the instantiation without it, which scales the
-// products in fp32 with an fma in front of every exp2.)
+// That is the instantiation with the template flag SCALED_Q, chosen by tsa_desc.fast_scale; the default
+// one scales the products in fp32 with an fma in front of every exp2.
 // The template also holds the layout with 64 rows per wavefront (QS = 2: four wavefronts, one
 // per SIMD, every LDS fragment feeds two MFMAs); it measures slower and is not instantiated
 // by default.
@@ -837,9 +837,9 @@ hipError_t launch_any(AttendArgs& a, int d, hipStream_t st) {
 
 hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
                          const void* Vt, const int32_t* block_list, int block_size, int max_blocks_per_row,
-                         int block_list_per_head, int exact_scale, void* Oc, float* lse, hipStream_t st) {
+                         int block_list_per_head, int fast_scale, void* Oc, float* lse, hipStream_t st) {
   AttendArgs a;
-  a.exact = exact_scale;
+  a.exact = fast_scale ? 0 : 1;
   a.block = block_list ? block_size : BM;
   a.bl_head_stride = block_list_per_head ? (long long)((Lc + a.block - 1) / a.block) * max_blocks_per_row : 0;
   a.Q = (const __bf16*)Qc; a.K = (const __bf16*)Kc; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
@@ -857,7 +857,7 @@ hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, con
                                const int32_t* k_dev) {
   AttendArgs a;
   a.k_dev = k_dev;
-  a.exact = dm.exact_scale;
+  a.exact = dm.fast_scale ? 0 : 1;
   a.block = block_list ? block_size : BM;
   a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
   a.lse = nullptr; a.block_list = block_list; a.max_blocks = max_blocks_per_row;

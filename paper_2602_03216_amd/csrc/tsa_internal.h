@@ -33,7 +33,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 // Shapes every launcher gets (validated by the C-ABI layer before any launch).
 struct Dims {
-  int B, Hq, Hkv, L, d, last_q, pool_w, group_mode, force_first, force_last, block_list_per_head, exact_scale;
+  int B, Hq, Hkv, L, d, last_q, pool_w, group_mode, force_first, force_last, block_list_per_head, fast_scale;
   float scale;
 };
 
@@ -91,7 +91,7 @@ hipError_t launch_compress_tiled(const Dims& dm, const void* Q, const void* K, c
 // attend.hip
 hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
                          const void* Vt, const int32_t* block_list, int block_size, int max_blocks_per_row,
-                         int block_list_per_head, int exact_scale, void* Oc, float* lse, hipStream_t st);
+                         int block_list_per_head, int fast_scale, void* Oc, float* lse, hipStream_t st);
 
 // attend.hip, fused form used by tsa_forward: Q and K are the original tensors, rows are gathered
 // through idx inside the kernel's loads; Vt = tiles of the gathered V (launch_compress_tiled with
