@@ -325,6 +325,50 @@ def test_forward_small(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant, fast_scale)
     assert not gu.from_dev(O)[np.repeat(~sel, Hq // Hs, axis=1)].any()
 
 
+def test_select_and_budget_random_sweep(tsa):
+    """Seeded sweep: 60 random shapes (1 to 140000 tokens, one to three batch entries, both selection
+    modes, forced tokens) on four kinds of scores (uniform, a handful of distinct values, signed zeros
+    only, a long tail with a repeated value): index sets, inverse maps and budgets bit-exact."""
+    r = _rng(31)
+    for i in range(60):
+        B = int(r.choice([1, 1, 2, 3])); Hkv = int(r.choice([1, 2, 4])); Hq = Hkv * int(r.choice([1, 2, 4])); gm = int(r.integers(0, 2))
+        L = int(r.choice([r.integers(1, 300), r.integers(300, 20000), r.integers(20000, 140000)]))
+        k = int(r.integers(1, L + 1)); ff = int(r.choice([0, 0, 3])); fl = int(r.choice([0, 0, 5]))
+        if ff + fl > min(k, L):
+            ff = fl = 0
+        kind = i % 4
+        if kind == 0:
+            s = r.random((B, Hq, L)).astype(np.float32)
+        elif kind == 1:
+            s = (r.integers(0, 4, (B, Hq, L)) / 4.0).astype(np.float32)
+        elif kind == 2:
+            s = np.where(r.random((B, Hq, L)) < 0.5, 0.0, -0.0).astype(np.float32)
+        else:
+            s = (r.random((B, Hq, L)) ** 8).astype(np.float32)
+            s[..., ::7] = s[..., 0:1]
+        desc = tsa.make_desc(B, Hq, Hkv, L, 128, min(64, L), group_mode=gm, force_first=ff, force_last=fl)
+        Hs = Hkv if gm else Hq
+        sd = torch.from_numpy(s).to(gu.DEV)
+        idx = torch.full((B, Hs, k), -7, dtype=torch.int32, device=gu.DEV)
+        inv = torch.full((B, Hs, L), -7, dtype=torch.int32, device=gu.DEV)
+        tsa.tsa_select(desc, sd, k, idx, inv, _ws(tsa, desc, k))
+        sel = s
+        if gm:          # the library sums the heads of a group in float32, in head order
+            g = Hq // Hkv
+            sel = np.zeros((B, Hkv, L), dtype=np.float32)
+            for j in range(g):
+                sel = (sel + s.reshape(B, Hkv, g, L)[:, :, j]).astype(np.float32)
+        widx, winv = orc.select(sel.astype(np.float64), k, force_first=ff, force_last=fl)
+        what = (B, Hq, Hkv, gm, L, k, ff, fl, kind)
+        assert np.array_equal(idx.cpu().numpy(), widx), what
+        assert np.array_equal(inv.cpu().numpy(), winv), what
+        if s.sum() > 0:
+            tau = float(r.choice([0.0, 1e-3, 0.01, 0.3, 0.77, 1.0]))
+            kk = torch.zeros(B, dtype=torch.int32, device=gu.DEV)
+            tsa.tsa_coverage_budget(desc, sd, tau, kk, _ws(tsa, desc, 1))
+            assert np.array_equal(kk.cpu().numpy(), orc.coverage_budget(s, tau)), (what, tau)
+
+
 def _random_forward_cases(n, seed):
     r = np.random.Generator(np.random.PCG64(seed))
     cases = []
