@@ -2,7 +2,9 @@
  * libtsa -- Token Sparse Attention prefill hot path for AMD MI355X (gfx950).
  *
  * C ABI.  Every tensor argument is a DEVICE pointer owned by the caller, 16-byte
- * aligned, contiguous row-major in the stated shape; bf16 tensors are passed as
+ * aligned, contiguous row-major in the stated shape (the full-length tensors Q, K,
+ * V and O may instead follow the strides of the descriptor, wherever an entry point
+ * takes them in full length); bf16 tensors are passed as
  * `const void*` / `void*` (2 bytes per element).  The library never allocates or
  * frees device memory: scratch space comes in through the `ws` argument (256-byte
  * aligned), sized with tsa_workspace_bytes() or the entry point's own size query.
@@ -60,6 +62,16 @@ typedef struct tsa_desc {
                            the QK product as Q * (scale * log2 e) rounded to bf16, which saves the attention
                            loop one multiplication per score (about 5 % faster) at the price of one more
                            rounding of the queries: see tsa_attend */
+  /* Layout of the full-length tensors Q [B,Hq,L,d], K and V [B,Hkv,L,d] (one layout for both) and
+   * O [B,Hq,L,d], in elements: element (b, h, t, c) sits at b * stride_b + h * stride_h + t * stride_l + c.
+   * All three strides of a tensor zero (the default) means contiguous [B,H,L,d]; a [B,L,H,d] tensor (the
+   * layout a fused QKV projection leaves behind) is stride_b = L*H*d, stride_h = d, stride_l = H*d.
+   * Every stride must be a multiple of 8 (rows stay 16-byte aligned), stride_l >= d, and L * stride_l
+   * below 2^30 elements.  Compacted tensors, scores, index sets, workspaces and the residual stream are
+   * always contiguous in the shapes stated at their entry points. */
+  int64_t q_stride_b, q_stride_h, q_stride_l;
+  int64_t kv_stride_b, kv_stride_h, kv_stride_l;
+  int64_t o_stride_b, o_stride_h, o_stride_l;
 } tsa_desc;
 
 /* Version of this ABI (increases when a signature changes). */

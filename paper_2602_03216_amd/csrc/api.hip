@@ -48,6 +48,24 @@ int check_desc(const tsa_desc* d, tsa::Dims* out) {
   out->block_list_per_head = d->block_list_per_head;
   out->fast_scale = d->fast_scale;
   out->scale = d->scale > 0.0f ? d->scale : 1.0f / std::sqrt((float)d->d);
+  struct { const char* name; int64_t b, h, l; int heads; tsa::Strides* dst; } lay[3] = {
+      {"q", d->q_stride_b, d->q_stride_h, d->q_stride_l, d->Hq, &out->q},
+      {"kv", d->kv_stride_b, d->kv_stride_h, d->kv_stride_l, d->Hkv, &out->kv},
+      {"o", d->o_stride_b, d->o_stride_h, d->o_stride_l, d->Hq, &out->o}};
+  for (auto& t : lay) {
+    if (t.b == 0 && t.h == 0 && t.l == 0) {
+      *t.dst = tsa::Strides{(long long)t.heads * d->L * d->d, (long long)d->L * d->d, (long long)d->d};
+      continue;
+    }
+    if (t.b < 0 || t.h < 0 || t.l < d->d || (t.b | t.h | t.l) % 8 != 0)
+      return fail(TSA_ERR_ARG, "%s strides: multiples of 8 elements, stride_l >= d, none negative (or all three 0)", t.name);
+    if ((d->Hq > 1 || d->Hkv > 1) && t.heads > 1 && t.h == 0) return fail(TSA_ERR_ARG, "%s_stride_h is 0", t.name);
+    if (d->B > 1 && t.b == 0) return fail(TSA_ERR_ARG, "%s_stride_b is 0", t.name);
+    // rows of one head are addressed with 32-bit byte offsets inside the kernels
+    if ((long long)d->L * t.l >= (1LL << 30)) return fail(TSA_ERR_UNSUPPORTED, "%s: L * stride_l must stay below 2^30 elements", t.name);
+    if (t.l >= (1LL << 23) || d->L >= (1 << 24)) return fail(TSA_ERR_UNSUPPORTED, "%s: stride_l must stay below 2^23 elements and L below 2^24", t.name);
+    *t.dst = tsa::Strides{(long long)t.b, (long long)t.h, (long long)t.l};
+  }
   return TSA_OK;
 }
 
@@ -113,7 +131,7 @@ ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
 
 extern "C" {
 
-int tsa_version(void) { return 7; }
+int tsa_version(void) { return 8; }
 
 const char* tsa_last_error(void) { return g_err; }
 

@@ -65,6 +65,7 @@ struct AttendArgs {
   int exact;                   // 1: scores scaled in fp32 (host side only: selects the kernel)
   int BH, Hq, kvh, Lc, nq_tiles, nk_tiles;
   const int32_t* k_dev;        // fused form: compacted rows per batch entry, decided on the device (NULL: Lc)
+  Strides qs, ks, os;          // fused form: layouts of the original Q, K and of the full-length output (elements)
   float c;                     // scale * log2(e)
   // Fused form (gather in the loads, scatter in the epilogue): Q and K are the ORIGINAL tensors of
   // L tokens (K with Hkv heads), compacted row r of selection row `sel` is token idx[sel][r];
@@ -352,12 +353,14 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const long long bh = (long long)b * a.Hq + h;
   const long long bkv = (long long)b * a.kvh + h / g;    // head of K^ / V^ (fused: of the index set and the V tiles)
   // rows of Q and K: the compacted tensors, or (fused) the original ones addressed through idx
+  // (fused: row pitch and head offsets come from the caller's layout; byte offsets of a row fit 32 bits
+  // and both factors of token * pitch fit 24 bits, checked on the host)
+  const int q_pitch = FUSED ? (int)a.qs.l * 2 : ROWB, k_pitch = FUSED ? (int)a.ks.l * 2 : ROWB;
+  const __bf16* q_head = FUSED ? a.Q + a.qs.head(b, h) : a.Q + bh * Lc * D;
+  const __bf16* k_head = FUSED ? a.K + a.ks.head(b, h / g_grp) : a.K + bkv * Lc * D;
   const int n_rows = FUSED ? a.L : Lc;
-  const long long head_bytes = (long long)n_rows * ROWB;
-  const long long k_head = FUSED ? (long long)b * a.Hkv + h / g_grp : bkv;
-
-  const __amdgpu_buffer_rsrc_t Qr = head_rsrc(a.Q + bh * n_rows * D, head_bytes);
-  const __amdgpu_buffer_rsrc_t Kr = head_rsrc(a.K + k_head * n_rows * D, head_bytes);
+  const __amdgpu_buffer_rsrc_t Qr = head_rsrc(q_head, (long long)n_rows * q_pitch);
+  const __amdgpu_buffer_rsrc_t Kr = head_rsrc(k_head, (long long)n_rows * k_pitch);
   const long long vt_bytes = (long long)a.nk_tiles * BN * ROWB;
   const __amdgpu_buffer_rsrc_t Vr = head_rsrc(a.Vt + bkv * (vt_bytes / 2), vt_bytes);
   const int32_t* idx_row = FUSED ? a.idx + bkv * a.Lc : nullptr;
@@ -382,6 +385,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   // before the epilogue.
   constexpr int LPR = D / 8, RPP = kThreads / LPR;
   const bool zfill = FUSED && a.Of != nullptr;
+  const long long o_pitch16 = FUSED ? a.os.l / 8 : LPR;          // 16-byte pieces between rows of the full-length output
   const int32_t* inv_row = nullptr;
   u32x4* zrow = nullptr;
   int z_hi = 0, zt = 0, zr = 0;                          // end of the range, next row of this thread, its inv entry
@@ -390,13 +394,13 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     inv_row = a.inv + bkv * a.L;
     const int tok_lo = qt == 0 ? 0 : idx_row[q0];
     z_hi = q0 + BM >= Lc ? a.L : idx_row[q0 + BM];
-    zrow = (u32x4*)(a.Of + bh * a.L * D) + (tid % LPR);
+    zrow = (u32x4*)(a.Of + a.os.head(b, h)) + (tid % LPR);
     zt = tok_lo + tid / LPR;
     zr = zt < z_hi ? inv_row[zt] : 0;
     z_passes = (z_hi - tok_lo + RPP - 1) / RPP;
   }
   auto zero_step = [&]() {
-    if (zr < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)zt * LPR);
+    if (zr < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)zt * o_pitch16);
     zt += RPP;
     zr = zt < z_hi ? inv_row[zt] : 0;
   };
@@ -408,7 +412,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     int qrow_off = (wrow0 + 32 * qs + lo) * ROWB;
     if (FUSED) {
       const int qr = wrow0 + 32 * qs + lo;
-      qrow_off = qr < Lc ? idx_row[qr] * ROWB : a.L * ROWB;   // past the end: out of the buffer's range, reads zeros
+      qrow_off = qr < Lc ? (int)__umul24(idx_row[qr], q_pitch) : a.L * q_pitch;   // past the end: out of the buffer's range, reads zeros
     }
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
@@ -482,6 +486,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   // Rows of the next K tile to be loaded: ktok[i] = row of thread chunk i (fused: the token the
   // compacted row stands for, fetched from idx one tile ahead of the K load that uses it).
   int ktok[CH];
+  auto row_off = [&](int tok) -> int { return FUSED ? (int)__umul24(tok, k_pitch) : tok * ROWB; };
   auto fetch_tok = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
@@ -492,7 +497,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   auto load_k = [&](u32x4 (&reg)[CH]) {
 #pragma unroll
     for (int i = 0; i < CH; ++i)
-      reg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, ktok[i] * ROWB + 16 * st_col, 0, 0);
+      reg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, row_off(ktok[i]) + 16 * st_col, 0, 0);
   };
   auto load_v = [&](int k0, u32x4 (&reg)[CH]) {
 #pragma unroll
@@ -684,7 +689,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
         if (blk == 3) {                 // K(t+2) -> kf, V(t+1) -> vn, then refill the registers
           if (i < CH) {
             *(u32x4*)(&kf[lk_off + i * kRowsPerPass * KS]) = kreg[i];
-            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, ktok[i] * ROWB + 16 * st_col, 0, 0);
+            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(Kr, row_off(ktok[i]) + 16 * st_col, 0, 0);
             if (FUSED) ktok[i] = __builtin_amdgcn_raw_buffer_load_b32(Ir, (st_row + i * kRowsPerPass) * 4, tokload * 4, 0);
             else ktok[i] = tokload + st_row + i * kRowsPerPass;
           } else if (i < 2 * CH) {
@@ -769,14 +774,14 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   // ---- fused form: the zero rows the tile loop did not get to, eight look-ups in flight per thread
   if (zfill) {
     constexpr int kBatch = 8;
-    if (zr < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)zt * LPR);
+    if (zr < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)zt * o_pitch16);
     for (int t0 = zt + RPP; t0 < z_hi; t0 += kBatch * RPP) {
       int r[kBatch];
 #pragma unroll
       for (int j = 0; j < kBatch; ++j) r[j] = t0 + j * RPP < z_hi ? inv_row[t0 + j * RPP] : 0;
 #pragma unroll
       for (int j = 0; j < kBatch; ++j)
-        if (r[j] < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)(t0 + j * RPP) * LPR);
+        if (r[j] < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)(t0 + j * RPP) * o_pitch16);
     }
   }
 
@@ -790,7 +795,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
       __bf16* orow = a.O ? a.O + (bh * a.Lc + qrow) * D : nullptr;
       __bf16* frow = nullptr;                       // fused: the token's row of the full-length output
       __bf16* xrow = nullptr;                       // fused: the token's slice of the residual stream
-      if (FUSED && a.Of) frow = a.Of + (bh * a.L + idx_row[qrow]) * D;
+      if (FUSED && a.Of) frow = a.Of + a.os.head(b, h) + idx_row[qrow] * a.os.l;
       if (FUSED && a.X) xrow = a.X + (((long long)b * a.L + idx_row[qrow]) * a.Hq + h) * D;
 #pragma unroll
       for (int dt = 0; dt < ND; ++dt)
@@ -848,6 +853,7 @@ hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale
   a.c = scale * kLog2e;
   a.idx = nullptr; a.inv = nullptr; a.Of = nullptr; a.X = nullptr; a.L = Lc; a.Hkv = kv_heads;
   a.k_dev = nullptr;
+  a.qs = a.ks = a.os = Strides{0, 0, 0};
   return launch_any<false>(a, d, st);
 }
 
@@ -857,6 +863,7 @@ hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, con
                                const int32_t* k_dev) {
   AttendArgs a;
   a.k_dev = k_dev;
+  a.qs = dm.q; a.ks = dm.kv; a.os = dm.o;
   a.exact = dm.fast_scale ? 0 : 1;
   a.block = block_list ? block_size : BM;
   a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;

@@ -11,13 +11,39 @@ namespace {
 
 constexpr int kThreads = 256;
 
+// strides of a full-length tensor in 16-byte pieces (the kernels below move u32x4)
+inline Strides pieces(const Strides& s) { return Strides{s.b / 8, s.h / 8, s.l / 8}; }
+
+// Where row (bh, t) of the full-length output starts, in 16-byte pieces.  The contiguous layout keeps the
+// plain product (no division by the head count in kernels that run at the memory rate).
+struct OutMap {
+  Strides s;
+  int H, L, contiguous;
+  __device__ __forceinline__ long long row(long long bh, int t) const {
+    if (contiguous) return (bh * L + t) * s.l;
+    const int i = (int)bh;                    // B * Hq is at most 65535
+    return s.head(i / H, i % H) + t * s.l;
+  }
+  __device__ __forceinline__ long long flat(long long task) const {   // task = bh * L + t
+    if (contiguous) return task * s.l;
+    const int i = (int)(task / L);
+    return s.head(i / H, i % H) + (task - (long long)i * L) * s.l;
+  }
+};
+inline OutMap out_map(const Dims& dm) {
+  OutMap m;
+  m.s = pieces(dm.o); m.H = dm.Hq; m.L = dm.L;
+  m.contiguous = dm.o.h == (long long)dm.L * dm.o.l && dm.o.b == (long long)dm.Hq * dm.o.h;
+  return m;
+}
+
 // One task = one compacted row (b, h, r): copy Q[b,h,S[r],:] -> Qc[b,h,r,:] and the K, V rows
 // of KV head h/g.  LPR lanes per row (d/8).
 template <int LPR>
 __global__ __launch_bounds__(kThreads) void compress_kernel(
     const u32x4* __restrict__ Q, const u32x4* __restrict__ K, const u32x4* __restrict__ V,
     const int32_t* __restrict__ idx, u32x4* __restrict__ Qc, u32x4* __restrict__ Kc, u32x4* __restrict__ Vc,
-    int Hq, int Hkv, int L, int k, int group_mode, long long n_tasks) {
+    int Hq, int Hkv, int L, int k, int group_mode, long long n_tasks, Strides qs, Strides ks) {
   const long long gtid = (long long)blockIdx.x * kThreads + threadIdx.x;
   const long long task = gtid / LPR;
   const int lane = (int)(gtid % LPR);
@@ -32,13 +58,14 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
   const long long sel_head = group_mode ? bkv : bh;
   const int t = idx[sel_head * k + r];
   // LPR 16-byte units per row
-  Qc[(bh * k + r) * LPR + lane] = Q[(bh * L + t) * LPR + lane];
+  const long long kv_at = ks.head(b, kv) + t * ks.l + lane;
+  Qc[(bh * k + r) * LPR + lane] = Q[qs.head(b, h) + t * qs.l + lane];
   if (group_mode == 0) {
-    Kc[(bh * k + r) * LPR + lane] = K[(bkv * L + t) * LPR + lane];
-    Vc[(bh * k + r) * LPR + lane] = V[(bkv * L + t) * LPR + lane];
+    Kc[(bh * k + r) * LPR + lane] = K[kv_at];
+    Vc[(bh * k + r) * LPR + lane] = V[kv_at];
   } else if (h % g == 0) {
-    Kc[(bkv * k + r) * LPR + lane] = K[(bkv * L + t) * LPR + lane];
-    Vc[(bkv * k + r) * LPR + lane] = V[(bkv * L + t) * LPR + lane];
+    Kc[(bkv * k + r) * LPR + lane] = K[kv_at];
+    Vc[(bkv * k + r) * LPR + lane] = V[kv_at];
   }
 }
 
@@ -50,7 +77,7 @@ constexpr int kStrideSkew = 1000;   // rows added to the quarter-tensor spacing 
 template <int LPR>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const u32x4* __restrict__ Oc, const int32_t* __restrict__ inv, u32x4* __restrict__ O,
-    int Hq, int g_sel, int L, int k, long long n_tasks, long long stride_tasks) {
+    int Hq, int g_sel, int L, int k, long long n_tasks, long long stride_tasks, OutMap om) {
   const long long gtid = (long long)blockIdx.x * kThreads + threadIdx.x;
   const long long task0 = gtid / LPR;
   const int lane = (int)(gtid % LPR);
@@ -77,7 +104,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
 #pragma unroll
   for (int j = 0; j < kRowsPerThread; ++j) {
     const long long task = task0 + j * stride_tasks;
-    if (task < n_tasks) __builtin_nontemporal_store(v[j], &O[(bh[j] * L + t[j]) * LPR + lane]);
+    if (task < n_tasks) __builtin_nontemporal_store(v[j], &O[om.row(bh[j], t[j]) + lane]);
   }
 }
 
@@ -88,7 +115,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
 template <int LPR>
 __global__ __launch_bounds__(kThreads) void decompress_split_kernel(
     const u32x4* __restrict__ Oc, const int32_t* __restrict__ idx, const int32_t* __restrict__ inv, u32x4* __restrict__ O,
-    int g_sel, int L, int k, long long n_copy, long long n_rows, unsigned copy_blocks) {
+    int g_sel, int L, int k, long long n_copy, long long n_rows, unsigned copy_blocks, OutMap om) {
   if (blockIdx.x < copy_blocks) {
     const long long gtid = (long long)blockIdx.x * kThreads + threadIdx.x;
     const long long task = gtid / LPR;               // (bh, r)
@@ -98,7 +125,7 @@ __global__ __launch_bounds__(kThreads) void decompress_split_kernel(
     const long long bh = task / k;
     const int t = idx[(bh / g_sel) * k + r];
     const u32x4 v = Oc[task * LPR + lane];
-    __builtin_nontemporal_store(v, &O[(bh * L + t) * LPR + lane]);
+    __builtin_nontemporal_store(v, &O[om.row(bh, t) + lane]);
     return;
   }
   const long long gtid = (long long)(blockIdx.x - copy_blocks) * kThreads + threadIdx.x;
@@ -116,7 +143,7 @@ __global__ __launch_bounds__(kThreads) void decompress_split_kernel(
 #pragma unroll
   for (int j = 0; j < kRowsPerThread; ++j) {
     const long long task = task0 + j * stride;
-    if (r[j] < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, &O[task * LPR + lane]);
+    if (r[j] < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, &O[om.flat(task) + lane]);
   }
 }
 
@@ -210,6 +237,7 @@ struct CompressTiledArgs {
   int Hq, Hkv, L, k, group_mode, nk_tiles;
   const int32_t* k_dev;       // count per batch entry decided on the device (NULL: k); rows of idx and the tile
                               // arrays keep the stride of k
+  Strides qs, ks;             // layouts of Q and of K / V, in 16-byte pieces
 };
 
 template <int D>
@@ -237,10 +265,11 @@ __global__ __launch_bounds__(kThreads) void compress_tiled_kernel(CompressTiledA
     const int tk = tok[r];
     u32x4 v = {0u, 0u, 0u, 0u};
     if (tk >= 0) {
-      if (a.Qc) a.Qc[(bh * a.k + r0 + r) * LPR + col] = a.Q[(bh * a.L + tk) * LPR + col];
+      if (a.Qc) a.Qc[(bh * a.k + r0 + r) * LPR + col] = a.Q[a.qs.head(b, h) + tk * a.qs.l + col];
       if (kv_owner) {
-        if (a.Qc) a.Kc[(sel_head * a.k + r0 + r) * LPR + col] = a.K[(bkv * a.L + tk) * LPR + col];
-        v = a.V[(bkv * a.L + tk) * LPR + col];
+        const long long kv_at = a.ks.head(b, h / g) + tk * a.ks.l + col;
+        if (a.Qc) a.Kc[(sel_head * a.k + r0 + r) * LPR + col] = a.K[kv_at];
+        v = a.V[kv_at];
       }
     }
     tile_put<D>(tile, r, col, v);
@@ -262,9 +291,9 @@ hipError_t launch_compress(const Dims& dm, const void* Q, const void* K, const v
   auto q = (const u32x4*)Q; auto k = (const u32x4*)K; auto v = (const u32x4*)V;
   auto qc = (u32x4*)Qc; auto kc = (u32x4*)Kc; auto vc = (u32x4*)Vc;
   if (dm.d == 128)
-    compress_kernel<16><<<blocks_for(n, 16), kThreads, 0, st>>>(q, k, v, idx, qc, kc, vc, dm.Hq, dm.Hkv, dm.L, k_keep, dm.group_mode, n);
+    compress_kernel<16><<<blocks_for(n, 16), kThreads, 0, st>>>(q, k, v, idx, qc, kc, vc, dm.Hq, dm.Hkv, dm.L, k_keep, dm.group_mode, n, pieces(dm.q), pieces(dm.kv));
   else
-    compress_kernel<8><<<blocks_for(n, 8), kThreads, 0, st>>>(q, k, v, idx, qc, kc, vc, dm.Hq, dm.Hkv, dm.L, k_keep, dm.group_mode, n);
+    compress_kernel<8><<<blocks_for(n, 8), kThreads, 0, st>>>(q, k, v, idx, qc, kc, vc, dm.Hq, dm.Hkv, dm.L, k_keep, dm.group_mode, n, pieces(dm.q), pieces(dm.kv));
   return hipGetLastError();
 }
 
@@ -280,6 +309,7 @@ hipError_t launch_compress_tiled(const Dims& dm, const void* Q, const void* K, c
                                  int k_keep, void* Qc, void* Kc, void* Vt, hipStream_t st, const int32_t* k_dev) {
   CompressTiledArgs a;
   a.k_dev = k_dev;
+  a.qs = pieces(dm.q); a.ks = pieces(dm.kv);
   a.Q = (const u32x4*)Q; a.K = (const u32x4*)K; a.V = (const u32x4*)V; a.idx = idx;
   a.Qc = (u32x4*)Qc; a.Kc = (u32x4*)Kc; a.Vt = (__bf16*)Vt;
   a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.L = dm.L; a.k = k_keep; a.group_mode = dm.group_mode;
@@ -307,17 +337,17 @@ hipError_t launch_decompress(const Dims& dm, const void* Oc, const int32_t* idx,
     const long long n_copy = (long long)dm.B * dm.Hq * k_keep;
     if (dm.d == 128) {
       const unsigned cb = blocks_for(n_copy, 16);
-      decompress_split_kernel<16><<<cb + blocks_for(stride, 16), kThreads, 0, st>>>((const u32x4*)Oc, idx, inv, (u32x4*)O, g_sel, dm.L, k_keep, n_copy, n, cb);
+      decompress_split_kernel<16><<<cb + blocks_for(stride, 16), kThreads, 0, st>>>((const u32x4*)Oc, idx, inv, (u32x4*)O, g_sel, dm.L, k_keep, n_copy, n, cb, out_map(dm));
     } else {
       const unsigned cb = blocks_for(n_copy, 8);
-      decompress_split_kernel<8><<<cb + blocks_for(stride, 8), kThreads, 0, st>>>((const u32x4*)Oc, idx, inv, (u32x4*)O, g_sel, dm.L, k_keep, n_copy, n, cb);
+      decompress_split_kernel<8><<<cb + blocks_for(stride, 8), kThreads, 0, st>>>((const u32x4*)Oc, idx, inv, (u32x4*)O, g_sel, dm.L, k_keep, n_copy, n, cb, out_map(dm));
     }
     return hipGetLastError();
   }
   if (dm.d == 128)
-    decompress_kernel<16><<<blocks_for(stride, 16), kThreads, 0, st>>>((const u32x4*)Oc, inv, (u32x4*)O, dm.Hq, g_sel, dm.L, k_keep, n, stride);
+    decompress_kernel<16><<<blocks_for(stride, 16), kThreads, 0, st>>>((const u32x4*)Oc, inv, (u32x4*)O, dm.Hq, g_sel, dm.L, k_keep, n, stride, out_map(dm));
   else
-    decompress_kernel<8><<<blocks_for(stride, 8), kThreads, 0, st>>>((const u32x4*)Oc, inv, (u32x4*)O, dm.Hq, g_sel, dm.L, k_keep, n, stride);
+    decompress_kernel<8><<<blocks_for(stride, 8), kThreads, 0, st>>>((const u32x4*)Oc, inv, (u32x4*)O, dm.Hq, g_sel, dm.L, k_keep, n, stride, out_map(dm));
   return hipGetLastError();
 }
 

@@ -36,8 +36,8 @@ constexpr float kSumLimit = 1073741824.0f;   // 2^30: a unit's sum of exponentia
 constexpr int kMaxQueries = 128;
 
 struct ScoreArgs {
-  const __bf16* Q;             // scoring queries: row i of head bh at Q + bh * q_head_stride + (q_row0 + i) * d
-  long long q_head_stride;
+  const __bf16* Q;             // scoring queries: row i of head (b, h) at Q + qs.head(b, h) + (q_row0 + i) * qs.l
+  Strides qs, ks;              // layout of Q (or of the caller's query rows) and of K
   int q_row0;
   int min_pos;                 // smallest entry of qpos
   int qpos[kMaxQueries];       // position of scoring query i (ascending; query i sees keys t <= qpos[i]); padded with L - 1
@@ -57,7 +57,7 @@ __device__ __forceinline__ void load_q_frags(const ScoreArgs& a, long long bh, i
   for (int qt = 0; qt < NQT; ++qt) {
     const int qi = 32 * qt + lo;
     const bool ok = qi < a.Lq;
-    const __bf16* row = a.Q + bh * a.q_head_stride + (long long)(a.q_row0 + (ok ? qi : 0)) * D + 8 * hi;
+    const __bf16* row = a.Q + a.qs.head(bh / a.Hq, bh % a.Hq) + (long long)(a.q_row0 + (ok ? qi : 0)) * a.qs.l + 8 * hi;
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
       bf16x8 v = *(const bf16x8*)(row + 16 * s);
@@ -91,6 +91,7 @@ struct KStage {
   static constexpr int CH = kTK * (D / 8) / kThreads;
   static constexpr int kRowsPerPass = kThreads / (D / 8);
   const __bf16* Kh;
+  long long row_stride;        // elements between consecutive keys
   int L, st_row, st_col;
   u32x4 reg[CH];
   __device__ __forceinline__ void load(int k0) {
@@ -98,7 +99,7 @@ struct KStage {
     for (int i = 0; i < CH; ++i) {
       const int key = k0 + st_row + kRowsPerPass * i;
       u32x4 v = {0u, 0u, 0u, 0u};
-      if (key < L) v = *(const u32x4*)(Kh + (long long)key * D + 8 * st_col);
+      if (key < L) v = *(const u32x4*)(Kh + (long long)key * row_stride + 8 * st_col);
       reg[i] = v;
     }
   }
@@ -242,7 +243,8 @@ __global__ __launch_bounds__(kThreads, NQT <= 2 ? 2 : 1) void score_pass1(ScoreA
 #pragma unroll
   for (int qt = 0; qt < NQT; ++qt) my_pos[qt] = a.qpos[32 * qt + lo];
   KStage<D> stg;
-  stg.Kh = a.K + (bkv * (long long)a.L) * D;
+  stg.Kh = a.K + a.ks.head(b, kv);
+  stg.row_stride = a.ks.l;
   stg.L = a.L; stg.st_row = tid / (D / 8); stg.st_col = tid % (D / 8);
   const int k_rd = lo * KS + 8 * hi;
 
@@ -373,7 +375,8 @@ __global__ __launch_bounds__(kThreads, NQT <= 2 ? 2 : 1) void score_pass2(ScoreA
   const int c_begin = chunk * a.chunk, c_end = min(c_begin + a.chunk, a.L);
   const int sub_per_tile = (kTK / 32) / role.ksplit;
   KStage<D> stg;
-  stg.Kh = a.K + (bkv * (long long)a.L) * D;
+  stg.Kh = a.K + a.ks.head(b, kv);
+  stg.row_stride = a.ks.l;
   stg.L = a.L; stg.st_row = tid / (D / 8); stg.st_col = tid % (D / 8);
   const int k_rd = lo * KS + 8 * hi;
 
@@ -505,6 +508,7 @@ hipError_t launch_common(const Dims& dm, ScoreArgs& a, const void* K, float* sco
   const int nqt = nqt_for(dm.last_q);
   const int QP = 32 * nqt;
   a.K = (const __bf16*)K; a.scores = scores;
+  a.ks = dm.kv;
   a.Hq = dm.Hq; a.Hkv = dm.Hkv; a.L = dm.L; a.Lq = dm.last_q;
   a.chunk = chunk_for(dm);
   a.nchunks = (dm.L + a.chunk - 1) / a.chunk;
@@ -535,7 +539,7 @@ hipError_t launch_common(const Dims& dm, ScoreArgs& a, const void* K, float* sco
 hipError_t launch_score(const Dims& dm, const void* Q, const void* K, float* scores, void* ws, hipStream_t st) {
   ScoreArgs a;
   a.Q = (const __bf16*)Q;
-  a.q_head_stride = (long long)dm.L * dm.d;
+  a.qs = dm.q;
   a.q_row0 = dm.L - dm.last_q;
   a.min_pos = dm.L - dm.last_q;
   for (int i = 0; i < kMaxQueries; ++i) a.qpos[i] = i < dm.last_q ? dm.L - dm.last_q + i : dm.L - 1;
@@ -547,7 +551,7 @@ hipError_t launch_score_queries(const Dims& dm, const void* Qsel, const int32_t*
                                 void* ws, hipStream_t st) {
   ScoreArgs a;
   a.Q = (const __bf16*)Qsel;
-  a.q_head_stride = (long long)dm.last_q * dm.d;
+  a.qs = Strides{(long long)dm.Hq * dm.last_q * dm.d, (long long)dm.last_q * dm.d, (long long)dm.d};
   a.q_row0 = 0;
   a.min_pos = qpos[0];
   for (int i = 0; i < kMaxQueries; ++i) a.qpos[i] = i < dm.last_q ? qpos[i] : dm.L - 1;
@@ -561,6 +565,8 @@ namespace {
 struct GatherArgs {
   const u32x4* Q;
   u32x4* Qsel;
+  Strides qs;                  // layout of Q, in 16-byte pieces
+  int Hq;
   int L, n, lpr;               // lpr = 16-byte pieces per row
   int qpos[kMaxQueries];
 };
@@ -573,7 +579,7 @@ __global__ void gather_queries_kernel(GatherArgs a, long long n_pieces) {
   const long long row = i / a.lpr;
   const int j = (int)(row % a.n);
   const long long bh = row / a.n;
-  a.Qsel[i] = a.Q[(bh * a.L + a.qpos[j]) * a.lpr + piece];
+  a.Qsel[i] = a.Q[a.qs.head(bh / a.Hq, bh % a.Hq) + a.qpos[j] * a.qs.l + piece];
 }
 
 // Segment j of the query-only pooling: rows floor(j L / n) .. ceil((j+1) L / n) - 1.
@@ -588,7 +594,7 @@ __device__ __forceinline__ void segment(int j, int L, int n, int& lo, int& hi) {
 constexpr int kPoolThreads = 256;
 template <int D>
 __global__ __launch_bounds__(kPoolThreads) void pool_queries_partial(const u32x4* __restrict__ Q, float* __restrict__ part,
-                                                                     int L, int n_pool, int n_split) {
+                                                                     int L, int n_pool, int n_split, Strides qs, int Hq) {
   constexpr int LPR = D / 8, RPP = kPoolThreads / LPR;      // rows per pass
   __shared__ float red[RPP][D];
   const int s = blockIdx.x, j = blockIdx.y;
@@ -600,7 +606,7 @@ __global__ __launch_bounds__(kPoolThreads) void pool_queries_partial(const u32x4
   const int piece = threadIdx.x % LPR, rr = threadIdx.x / LPR;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   for (int r = r_begin + rr; r < r_end; r += RPP) {
-    const u32x4 v = Q[(bh * L + r) * LPR + piece];
+    const u32x4 v = Q[qs.head(bh / Hq, bh % Hq) + r * qs.l + piece];       // qs in 16-byte pieces
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       acc[2 * c] += __uint_as_float(v[c] << 16);
@@ -642,6 +648,7 @@ inline int pool_split(int L, int n_pool) {
 hipError_t launch_gather_queries(const Dims& dm, const void* Q, const int32_t* qpos, int n, void* Qsel, hipStream_t st) {
   GatherArgs a;
   a.Q = (const u32x4*)Q; a.Qsel = (u32x4*)Qsel; a.L = dm.L; a.n = n; a.lpr = dm.d / 8;
+  a.qs = Strides{dm.q.b / 8, dm.q.h / 8, dm.q.l / 8}; a.Hq = dm.Hq;
   for (int i = 0; i < kMaxQueries; ++i) a.qpos[i] = i < n ? qpos[i] : 0;
   const long long pieces = (long long)dm.B * dm.Hq * n * a.lpr;
   gather_queries_kernel<<<(unsigned)((pieces + 255) / 256), 256, 0, st>>>(a, pieces);
@@ -655,8 +662,9 @@ size_t pool_queries_ws_bytes(const Dims& dm, int n_pool) {
 hipError_t launch_pool_queries(const Dims& dm, const void* Q, int n_pool, void* Qsel, void* ws, hipStream_t st) {
   const int n_split = pool_split(dm.L, n_pool);
   const dim3 grid((unsigned)n_split, (unsigned)n_pool, (unsigned)(dm.B * dm.Hq));
-  if (dm.d == 128) pool_queries_partial<128><<<grid, kPoolThreads, 0, st>>>((const u32x4*)Q, (float*)ws, dm.L, n_pool, n_split);
-  else pool_queries_partial<64><<<grid, kPoolThreads, 0, st>>>((const u32x4*)Q, (float*)ws, dm.L, n_pool, n_split);
+  const Strides qs8{dm.q.b / 8, dm.q.h / 8, dm.q.l / 8};
+  if (dm.d == 128) pool_queries_partial<128><<<grid, kPoolThreads, 0, st>>>((const u32x4*)Q, (float*)ws, dm.L, n_pool, n_split, qs8, dm.Hq);
+  else pool_queries_partial<64><<<grid, kPoolThreads, 0, st>>>((const u32x4*)Q, (float*)ws, dm.L, n_pool, n_split, qs8, dm.Hq);
   const long long n = (long long)dm.B * dm.Hq * n_pool * dm.d;
   pool_queries_final<<<(unsigned)((n + 255) / 256), 256, 0, st>>>((const float*)ws, (__bf16*)Qsel, dm.L, n_pool, n_split, dm.d, n);
   return hipGetLastError();

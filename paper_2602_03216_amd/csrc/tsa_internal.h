@@ -32,9 +32,16 @@ __device__ __forceinline__ int c_row(int r, int hi) { return 8 * (r >> 2) + 4 * 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Shapes every launcher gets (validated by the C-ABI layer before any launch).
+// Element (b, h, t, c) of a full-length tensor sits at b * b_ + h * h_ + t * l_ + c (elements).
+struct Strides {
+  long long b, h, l;
+  __host__ __device__ long long head(long long bi, long long hi) const { return bi * b + hi * h; }
+};
+
 struct Dims {
   int B, Hq, Hkv, L, d, last_q, pool_w, group_mode, force_first, force_last, block_list_per_head, fast_scale;
   float scale;
+  Strides q, kv, o;            // Q; K and V; O
 };
 
 // ---- launchers (each returns hipGetLastError() after queuing its kernels) ----

@@ -27,8 +27,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_desc_struct_matches_header(lib):
-    assert ctypes.sizeof(tsa.tsa_desc) == 52
-    assert lib.tsa_version() == 7
+    assert ctypes.sizeof(tsa.tsa_desc) == 128
+    assert lib.tsa_version() == 8
 
 
 def test_keep_count_matches_oracle_rule(lib):
