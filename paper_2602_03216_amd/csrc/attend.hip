@@ -21,12 +21,14 @@
 // The O rescale is lazy: the running max is only raised when a row's new max exceeds it by
 // more than 2^8, so most tiles skip the multiply over the whole accumulator; the final
 // division by the row sum makes the result independent of the max actually used.
-// With tsa_desc.fast_scale the exponent s * scale * log2(e) - m costs no vector instruction in the pipelined loop: Q is
-// multiplied by scale * log2(e) once when it is loaded (and rounded back to bf16, one more rounding
-// of relative size 2^-9 on the query side), and the first MFMA of every QK chain starts from the
-// accumulator -m instead of 0, so the chain delivers s - m and the loop applies exp2 to it directly.
-// That is the instantiation with the template flag SCALED_Q, chosen by tsa_desc.fast_scale; the default
-// one scales the products in fp32 with an fma in front of every exp2.
+// The exponent s * scale * log2(e) - m is formed in the PV block that follows a QK block (one fma per
+// score, in fp32, in place, next to MFMAs that have little other vector work beside them), so the
+// blocks with the exponentials apply exp2 to the half tile as it is; a raise of m in between shifts the
+// waiting half tile by the same amount.
+// With tsa_desc.fast_scale (template flag SCALED_Q) even that fma goes: Q is multiplied by
+// scale * log2(e) once when it is loaded (and rounded back to bf16, one more rounding of relative size
+// 2^-9 on the query side), and the first MFMA of every QK chain starts from the accumulator -m instead
+// of 0, so the chain itself delivers s - m.
 // The template also holds the layout with 64 rows per wavefront (QS = 2: four wavefronts, one
 // per SIMD, every LDS fragment feeds two MFMAs); it measures slower and is not instantiated
 // by default.
@@ -312,9 +314,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const __bf16* base, 
 // every LDS fragment feeds two MFMAs.  QS = 1: 8 wavefronts of 32 rows, two per SIMD, which share
 // the SIMD's issue slots (a lone wavefront issues one vector instruction every ~8 clocks, two
 // together one every ~5) at the price of one LDS fragment per MFMA.
-// SCALED_Q: Q is multiplied by scale * log2(e) and rounded to bf16 when it is loaded, and the pipelined
-// iteration holds its half tiles as s - m (see the head of the file); otherwise the products are scaled
-// in fp32 by an fma in front of every exp2.
+// SCALED_Q: Q is multiplied by scale * log2(e) and rounded to bf16 when it is loaded and the QK chains
+// start from -m (see the head of the file); otherwise the products are scaled in fp32 by an fma in the
+// PV blocks.  Either way the pipelined iteration holds its half tiles as s * c - m when their
+// exponentials are due.
 template <int D, int QS, bool FUSED, bool SCALED_Q>
 __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) {
   constexpr int kThreads = 512 / QS;
@@ -374,7 +377,8 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const int row_block = a.block_list ? a.block : BM;
   const int half_bit = 1 << ((RW * wave) / row_block);   // which row block of the query tile the wavefront is in
   const float c = SCALED_Q ? 1.0f : a.c;                 // scaled Q: the scores are already in exponent units
-  const float c_ = c;                                    // (the chunk loop of the pipelined iteration has its own c)
+  const float c_ = c;
+  const float inv_c = 1.0f / c;                                    // (the chunk loop of the pipelined iteration has its own c)
 
   // ---- fused form: zero rows of the full-length output.  The workgroup owns the tokens from its
   // first selected token up to the next workgroup's first one (the first workgroup of a head starts
@@ -592,9 +596,10 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   //    8..15  O^T += V^T(T0, half 0) pA  with  row max of sB          [then the rare raise of m]
   //   16..23  S^T(T1, half 0) -> sA      with  exp(sB) -> pB
   //   24..31  O^T += V^T(T0, half 1) pB  with  row max of sA, staging  [barrier, rare raise of m]
-  // Inside this loop sA and sB hold s - m (the QK chains start from -m), so the exponent is the
-  // accumulator itself and the row max is relative to m; a raise of m between the chain and its
-  // exponentials shifts the pending half tile by the same amount.
+  // Inside this loop sA and sB hold s * c - m by the time their exponentials are due (formed by an fma
+  // per element in the PV block after the chain, or, with scaled Q, by a chain that starts from -m), so the
+  // exponent is the register itself and the row max is relative to m; a raise of m between the two shifts
+  // the pending half tile by the same amount.
   // Each chunk consumes one 16-byte LDS fragment per lane (a K fragment or a V^T fragment);
   // fragments are fetched kPF chunks ahead through a small register ring that runs across the
   // blocks and across iterations, so the LDS latency is hidden.
@@ -653,8 +658,8 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
 #pragma unroll
           for (int e = 0; e < EPS; e += 2) {
             const int r = EPS * i + e;
-            const float p0 = SCALED_Q ? fast_exp2(s_in[qs][r]) : fast_exp2(fmaf(s_in[qs][r], c_, -m[qs]));
-            const float p1 = SCALED_Q ? fast_exp2(s_in[qs][r + 1]) : fast_exp2(fmaf(s_in[qs][r + 1], c_, -m[qs]));
+            const float p0 = fast_exp2(s_in[qs][r]);
+            const float p1 = fast_exp2(s_in[qs][r + 1]);
             if (r == 0) { ps0[qs] = p0; ps1[qs] = p1; }
             else { ps0[qs] += p0; ps1[qs] += p1; }
             p_out[qs][r >> 1] = pack_bf16(p0, p1);
@@ -670,15 +675,21 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
           }
         }
       } else {
-        const f32x16 (&s_in)[QS] = blk == 1 ? sB : sA;
+        f32x16 (&s_in)[QS] = blk == 1 ? sB : sA;
         const uint32_t (&pb)[QS][8] = blk == 1 ? pA : pB;
         const int hf = i / ND, dt = i % ND;
         constexpr int EPC = 16 / CPB;
         const bf16x8 vf = kfr[slot];
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
-          if (i == 0) mx[qs] = s_in[qs][0];
           o[qs][dt] = mfma32(vf, p_operand(pb[qs], hf), o[qs][dt]);
+          // exact scaling: the half tile that the last QK block left as plain scores becomes s * c - m here,
+          // two elements per chunk, next to the MFMAs of a PV block that has little else to do
+          if (!SCALED_Q) {
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) s_in[qs][EPC * i + e] = fmaf(s_in[qs][EPC * i + e], c_, -m[qs]);
+          }
+          if (i == 0) mx[qs] = s_in[qs][0];
           if (EPC == 2) mx[qs] = __builtin_fmaxf(__builtin_fmaxf(mx[qs], s_in[qs][2 * i]), s_in[qs][2 * i + 1]);
           else {
 #pragma unroll
@@ -703,18 +714,16 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
         }
         if (i == CPB - 1) {
 #pragma unroll
-          for (int qs = 0; qs < QS; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32)) * c_;
+          for (int qs = 0; qs < QS; ++qs) mxc[qs] = fmaxf(mx[qs], __shfl_xor(mx[qs], 32));
         }
       }
       __builtin_amdgcn_sched_barrier(0);
       if (c == 2 * CPB - 1) {
-        if (SCALED_Q) raise_max_rel<ND, QS>(mxc, m, negm, l, o, sB);
-        else raise_max<ND, QS>(mxc, m, l, o);
+        raise_max_rel<ND, QS>(mxc, m, negm, l, o, sB);
       }
     }
     lds_barrier();
-    if (SCALED_Q) raise_max_rel<ND, QS>(mxc, m, negm, l, o, sA);
-    else raise_max<ND, QS>(mxc, m, l, o);
+    raise_max_rel<ND, QS>(mxc, m, negm, l, o, sA);
     rotate();
     };
 
@@ -726,12 +735,11 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   auto pipelined = [&](const Tile& t) -> bool { return t.k0 >= 0 && t.use == gen.full && t.k0 + BN <= q0; };
   while (T0.k0 >= 0) {
     if (pipelined(T0) && pipelined(T1)) {
-      // the pipelined iterations hold their half tiles as s - m: sA enters and leaves in that form
-      if (SCALED_Q)
+      // the pipelined iterations hold their half tiles as s * c - m: sA enters and leaves in that form
 #pragma unroll
       for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { negm[qs][r] = -m[qs]; sA[qs][r] -= m[qs]; }
+        for (int r = 0; r < 16; ++r) { negm[qs][r] = -m[qs]; sA[qs][r] = fmaf(sA[qs][r], c_, -m[qs]); }
       prime_ring();
       do {
         const Tile T4 = gen.next();
@@ -740,11 +748,10 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
         T0 = T1; T1 = T2; T2 = T3; T3 = T4;
       } while (pipelined(T0) && pipelined(T1));
       if (T0.k0 < 0) break;
-      if (SCALED_Q)
 #pragma unroll
       for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sA[qs][r] += m[qs];
+        for (int r = 0; r < 16; ++r) sA[qs][r] = (sA[qs][r] + m[qs]) * inv_c;
     }
     qk_half<D, QS>(kc + 32 * KS, k_rd, qf, sB);
     if (wave_active(T0)) {
