@@ -61,7 +61,6 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
     Q, K, V = to_dev(inp.Q), to_dev(inp.K), to_dev(inp.V)
     B, Hq, Hkv, L, d, Lq = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"]
     desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq)
-    desc_fast = tsa.make_desc(B, Hq, Hkv, L, d, Lq, fast_scale=1)     # scaled queries rounded to bf16 (reported beside the default)
     O = torch.empty((B, Hq, L, d), dtype=torch.bfloat16, device=dev)
     out = {"workload": cfg["name"], "L": L, "Hq": Hq, "Hkv": Hkv, "d": d, "last_q": Lq, "per_tau": {}}
 
@@ -112,7 +111,6 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
             # the Q/K gather in its loads and the scatter in its epilogue), on the vt buffer of their own
             "v_tiles": lambda: tsa.tsa_compress_v_tiles(desc, V, idx, k, vt),
             "attend_fused": lambda: tsa.tsa_attend_fused(desc, Q, K, vt, idx, inv, k, O=O),
-            "attend_fused_fast_scale": lambda: tsa.tsa_attend_fused(desc_fast, Q, K, vt, idx, inv, k, O=O),
         }
         kk = torch.zeros(B, dtype=torch.int32, device=dev)
         parts["budget"] = lambda: tsa.tsa_coverage_budget(desc, scores, 0.005, kk, ws)   # the paper's tau for this model family
@@ -129,7 +127,6 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
             "v_tiles_ms": t["v_tiles"], "attend_fused_ms": t["attend_fused"],
             "attend_fused_tflops": w["attend_flops"] / t["attend_fused"] / 1e9,
             "attend_fused_frac_mfma_peak": w["attend_flops"] / t["attend_fused"] / 1e9 / MFMA_BF16_PEAK_TFLOPS,
-            "attend_fused_fast_scale_ms": t["attend_fused_fast_scale"],
             "budget_ms": t["budget"], "budget_k_keep_at_tau_cov_0.005": int(kk[0].item()),
             "speedup_attend_vs_dense": t_dense / t["attend"],
             "speedup_layer_vs_dense": t_dense / t_fwd,
@@ -355,7 +352,7 @@ def main():
         "speedup_attend_vs_own_dense": head["speedup_attend_vs_dense"],
         "ideal_attend_speedup": head["ideal_attend_speedup"],
         "dense_ms": r128["dense_ms"],
-        "roofline": {"kernel": "attend_kernel<128, 1, true, false> (tsa_attend_fused: the attention launch of tsa_forward; template arguments: d, query sub-tiles per wavefront, fused gather/scatter, scaled queries)",
+        "roofline": {"kernel": "attend_kernel<128, 1, true> (tsa_attend_fused: the attention launch of tsa_forward; template arguments: d, query sub-tiles per wavefront, fused gather/scatter)",
                      "bound": "mfma", "achieved": head["attend_fused_tflops"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": head["attend_fused_frac_mfma_peak"],
                      "flops_per_launch": w["attend_flops"], "avg_launch_ms": head["attend_fused_ms"],

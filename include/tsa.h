@@ -58,10 +58,6 @@ typedef struct tsa_desc {
   int32_t block_list_per_head; /* 0: one block list shared by all heads; 1: one list per (b, h),
                                   block_list is [B,Hq,ceil(Lc/block_size),max_blocks_per_row] (block-sparse
                                   methods pick a different pattern for every head) */
-  int32_t fast_scale;   /* attention only.  0 (default): the QK products are scaled in fp32; 1: the queries enter
-                           the QK product as Q * (scale * log2 e) rounded to bf16, which saves the attention
-                           loop one multiplication per score (about 5 % faster) at the price of one more
-                           rounding of the queries: see tsa_attend */
   /* Layout of the full-length tensors Q [B,Hq,L,d], K and V [B,Hkv,L,d] (one layout for both) and
    * O [B,Hq,L,d], in elements: element (b, h, t, c) sits at b * stride_b + h * stride_h + t * stride_l + c.
    * All three strides of a tensor zero (the default) means contiguous [B,H,L,d]; a [B,L,H,d] tensor (the
@@ -170,13 +166,7 @@ int tsa_compress(const tsa_desc* desc, const void* Q, const void* K, const void*
  *   operands want; Vc itself is not modified.
  * Arithmetic: bf16 MFMA with fp32 accumulation, online softmax in fp32, probabilities rounded
  * to bf16 before the PV product, output rounded to bf16 (nearest even); the products are scaled in
- * fp32.  With desc->fast_scale == 1 the queries instead enter the QK product as
- * Qc * (scale * log2 e) rounded to bf16 (nearest even), so that the products come out in the units
- * of the base-2 exponential: one rounding of relative size 2^-9 per query element, of the same size
- * as the one that made Qc bf16 in the first place; a logit moves by about
- * 2^-9 / sqrt(3) * scale * |q_i k_i|_2 (1e-3 for unit-variance rows, more where query and key norms
- * are large: with few keys and key rows of three times the usual norm an output element can move by
- * several 1e-2). */
+ * fp32. */
 size_t tsa_attend_workspace_bytes(const tsa_desc* desc, int32_t Lc, int32_t kv_heads);
 int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void* Vc,
                int32_t Lc, int32_t kv_heads,

@@ -31,17 +31,16 @@ class tsa_desc(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("L", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("last_q", ctypes.c_int32), ("pool_w", ctypes.c_int32),
                 ("group_mode", ctypes.c_int32), ("force_first", ctypes.c_int32), ("force_last", ctypes.c_int32),
-                ("scale", ctypes.c_float), ("block_list_per_head", ctypes.c_int32), ("fast_scale", ctypes.c_int32),
-                ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64), ("q_stride_l", ctypes.c_int64),
+                ("scale", ctypes.c_float), ("block_list_per_head", ctypes.c_int32), ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64), ("q_stride_l", ctypes.c_int64),
                 ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64), ("kv_stride_l", ctypes.c_int64),
                 ("o_stride_b", ctypes.c_int64), ("o_stride_h", ctypes.c_int64), ("o_stride_l", ctypes.c_int64)]
 
 
 def make_desc(B, Hq, Hkv, L, d, last_q=64, pool_w=1, group_mode=0, force_first=0, force_last=0, scale=0.0,
-              block_list_per_head=0, fast_scale=0, q_strides=(0, 0, 0), kv_strides=(0, 0, 0), o_strides=(0, 0, 0)):
+              block_list_per_head=0, q_strides=(0, 0, 0), kv_strides=(0, 0, 0), o_strides=(0, 0, 0)):
     """*_strides = (stride_b, stride_h, stride_l) in elements of Q, of K and V, of O; zeros = contiguous [B,H,L,d]."""
     return tsa_desc(B, Hq, Hkv, L, d, last_q, pool_w, group_mode, force_first, force_last, scale, block_list_per_head,
-                    fast_scale, *q_strides, *kv_strides, *o_strides)
+                    *q_strides, *kv_strides, *o_strides)
 
 
 def blhd_strides(H, L, d):

@@ -35,7 +35,6 @@ int check_desc(const tsa_desc* d, tsa::Dims* out) {
     return fail(TSA_ERR_ARG, "pool_w (%d) must be odd and lie in [1, 1023]", d->pool_w);
   if (d->group_mode != 0 && d->group_mode != 1) return fail(TSA_ERR_ARG, "group_mode must be 0 or 1");
   if (d->block_list_per_head != 0 && d->block_list_per_head != 1) return fail(TSA_ERR_ARG, "block_list_per_head must be 0 or 1");
-  if (d->fast_scale != 0 && d->fast_scale != 1) return fail(TSA_ERR_ARG, "fast_scale must be 0 or 1");
   if (d->force_first < 0 || d->force_last < 0 || (long long)d->force_first + d->force_last > d->L)
     return fail(TSA_ERR_ARG, "force_first / force_last out of range");
   if (!(d->scale >= 0.0f) || !std::isfinite(d->scale)) return fail(TSA_ERR_ARG, "scale must be finite and >= 0");
@@ -46,7 +45,6 @@ int check_desc(const tsa_desc* d, tsa::Dims* out) {
   out->last_q = d->last_q; out->pool_w = d->pool_w; out->group_mode = d->group_mode;
   out->force_first = d->force_first; out->force_last = d->force_last;
   out->block_list_per_head = d->block_list_per_head;
-  out->fast_scale = d->fast_scale;
   out->scale = d->scale > 0.0f ? d->scale : 1.0f / std::sqrt((float)d->d);
   struct { const char* name; int64_t b, h, l; int heads; tsa::Strides* dst; } lay[3] = {
       {"q", d->q_stride_b, d->q_stride_h, d->q_stride_l, d->Hq, &out->q},
@@ -131,7 +129,7 @@ ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
 
 extern "C" {
 
-int tsa_version(void) { return 8; }
+int tsa_version(void) { return 9; }
 
 const char* tsa_last_error(void) { return g_err; }
 
@@ -274,7 +272,7 @@ int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void*
   hipStream_t st = (hipStream_t)stream;
   if ((rc = hip_status(tsa::launch_v_tiles(dm.B, kv_heads, Lc, dm.d, Vc, ws, st), "tsa_attend(V tiles)"))) return rc;
   return hip_status(tsa::launch_attend(dm.B, dm.Hq, kv_heads, Lc, dm.d, dm.scale, Qc, Kc, ws, block_list,
-                                       block_size, max_blocks_per_row, dm.block_list_per_head, dm.fast_scale, Oc, lse, st), "tsa_attend");
+                                       block_size, max_blocks_per_row, dm.block_list_per_head, Oc, lse, st), "tsa_attend");
 }
 
 int tsa_decompress(const tsa_desc* desc, const void* Oc, const int32_t* idx, const int32_t* inv,

@@ -25,10 +25,6 @@
 // score, in fp32, in place, next to MFMAs that have little other vector work beside them), so the
 // blocks with the exponentials apply exp2 to the half tile as it is; a raise of m in between shifts the
 // waiting half tile by the same amount.
-// With tsa_desc.fast_scale (template flag SCALED_Q) even that fma goes: Q is multiplied by
-// scale * log2(e) once when it is loaded (and rounded back to bf16, one more rounding of relative size
-// 2^-9 on the query side), and the first MFMA of every QK chain starts from the accumulator -m instead
-// of 0, so the chain itself delivers s - m.
 // The template also holds the layout with 64 rows per wavefront (QS = 2: four wavefronts, one
 // per SIMD, every LDS fragment feeds two MFMAs); it measures slower and is not instantiated
 // by default.
@@ -64,7 +60,6 @@ struct AttendArgs {
   long long bl_head_stride;    // elements between the block lists of consecutive (b, h); 0 = one shared list
   int max_blocks;
   int block;                   // block size of the list: 64, 128 or 256 tokens
-  int exact;                   // 1: scores scaled in fp32 (host side only: selects the kernel)
   int BH, Hq, kvh, Lc, nq_tiles, nk_tiles;
   const int32_t* k_dev;        // fused form: compacted rows per batch entry, decided on the device (NULL: Lc)
   Strides qs, ks, os;          // fused form: layouts of the original Q, K and of the full-length output (elements)
@@ -242,11 +237,10 @@ __device__ __forceinline__ void raise_max(const float (&mxc)[QS], float (&m)[QS]
   }
 }
 
-// The same for a half tile held as s - m (the pipelined iteration subtracts the running max inside
-// the MFMA chain): mx is the row max relative to m.  A raise also shifts the pending half tile and
-// the chain-start vector negm (16 copies of -m, the C operand of the first MFMA of a chain).
+// The same for a half tile held as s * c - m (the form the pipelined iteration keeps between a QK block
+// and its exponentials): mx is the row max relative to m.  A raise also shifts the pending half tile.
 template <int ND, int QS>
-__device__ __forceinline__ void raise_max_rel(const float (&mx)[QS], float (&m)[QS], f32x16 (&negm)[QS], float (&l)[QS],
+__device__ __forceinline__ void raise_max_rel(const float (&mx)[QS], float (&m)[QS], float (&l)[QS],
                                               f32x16 (&o)[QS][ND], f32x16 (&pending)[QS]) {
   bool grow = false;
 #pragma unroll
@@ -259,7 +253,7 @@ __device__ __forceinline__ void raise_max_rel(const float (&mx)[QS], float (&m)[
       m[qs] += dlt;
       l[qs] *= alpha;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { negm[qs][r] = -m[qs]; pending[qs][r] -= dlt; }
+      for (int r = 0; r < 16; ++r) pending[qs][r] -= dlt;
 #pragma unroll
       for (int dt = 0; dt < ND; ++dt)
 #pragma unroll
@@ -314,11 +308,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t head_rsrc(const __bf16* base, 
 // every LDS fragment feeds two MFMAs.  QS = 1: 8 wavefronts of 32 rows, two per SIMD, which share
 // the SIMD's issue slots (a lone wavefront issues one vector instruction every ~8 clocks, two
 // together one every ~5) at the price of one LDS fragment per MFMA.
-// SCALED_Q: Q is multiplied by scale * log2(e) and rounded to bf16 when it is loaded and the QK chains
-// start from -m (see the head of the file); otherwise the products are scaled in fp32 by an fma in the
-// PV blocks.  Either way the pipelined iteration holds its half tiles as s * c - m when their
-// exponentials are due.
-template <int D, int QS, bool FUSED, bool SCALED_Q>
+template <int D, int QS, bool FUSED>
 __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) {
   constexpr int kThreads = 512 / QS;
   constexpr int RW = 32 * QS;                     // query rows per wavefront
@@ -376,7 +366,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const int wrow0 = q0 + RW * wave;                      // first query row of this wavefront
   const int row_block = a.block_list ? a.block : BM;
   const int half_bit = 1 << ((RW * wave) / row_block);   // which row block of the query tile the wavefront is in
-  const float c = SCALED_Q ? 1.0f : a.c;                 // scaled Q: the scores are already in exponent units
+  const float c = a.c;
   const float c_ = c;
   const float inv_c = 1.0f / c;                                    // (the chunk loop of the pipelined iteration has its own c)
 
@@ -428,15 +418,6 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   // loads as "possibly pending" into the main loop and makes every MFMA that reads a Q fragment
   // wait for the oldest in-flight K/V prefetch as well.
   __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0)
-  // Q is scaled by scale * log2(e) here, once, and rounded back to bf16: the scores then leave the
-  // MFMAs in the units of the exponent and the loop spends no multiplication on them.
-  if (SCALED_Q)
-#pragma unroll
-  for (int qs = 0; qs < QS; ++qs)
-#pragma unroll
-    for (int s = 0; s < NS; ++s)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qf[qs][s][e] = (__bf16)((float)qf[qs][s][e] * a.c);
 
   TileGen gen;
   gen.plain = a.block_list == nullptr;
@@ -628,7 +609,6 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   };
   // vload: byte offset of the V tile to prefetch (tile T2), tokload: first compacted row of the
   // K tile whose rows are looked up (tile T4)
-  f32x16 negm[QS];
   auto fast_iter = [&](const int vload, const int tokload) {
     float mxc[QS], mx[QS], ps0[QS], ps1[QS];
     f32x16 acc[QS];
@@ -653,7 +633,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
         // shadow of the MFMA that was just issued
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
-          if (i == 0) acc[qs] = SCALED_Q ? negm[qs] : f32x16{0};
+          if (i == 0) acc[qs] = f32x16{0};
           acc[qs] = mfma32(kfr[slot], qf[qs][i], acc[qs]);
 #pragma unroll
           for (int e = 0; e < EPS; e += 2) {
@@ -683,12 +663,10 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
 #pragma unroll
         for (int qs = 0; qs < QS; ++qs) {
           o[qs][dt] = mfma32(vf, p_operand(pb[qs], hf), o[qs][dt]);
-          // exact scaling: the half tile that the last QK block left as plain scores becomes s * c - m here,
-          // two elements per chunk, next to the MFMAs of a PV block that has little else to do
-          if (!SCALED_Q) {
+          // the half tile that the last QK block left as plain scores becomes s * c - m here, two elements
+          // per chunk, next to the MFMAs of a PV block that has little else to do
 #pragma unroll
-            for (int e = 0; e < EPC; ++e) s_in[qs][EPC * i + e] = fmaf(s_in[qs][EPC * i + e], c_, -m[qs]);
-          }
+          for (int e = 0; e < EPC; ++e) s_in[qs][EPC * i + e] = fmaf(s_in[qs][EPC * i + e], c_, -m[qs]);
           if (i == 0) mx[qs] = s_in[qs][0];
           if (EPC == 2) mx[qs] = __builtin_fmaxf(__builtin_fmaxf(mx[qs], s_in[qs][2 * i]), s_in[qs][2 * i + 1]);
           else {
@@ -719,11 +697,11 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
       }
       __builtin_amdgcn_sched_barrier(0);
       if (c == 2 * CPB - 1) {
-        raise_max_rel<ND, QS>(mxc, m, negm, l, o, sB);
+        raise_max_rel<ND, QS>(mxc, m, l, o, sB);
       }
     }
     lds_barrier();
-    raise_max_rel<ND, QS>(mxc, m, negm, l, o, sA);
+    raise_max_rel<ND, QS>(mxc, m, l, o, sA);
     rotate();
     };
 
@@ -739,7 +717,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
 #pragma unroll
       for (int qs = 0; qs < QS; ++qs)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { negm[qs][r] = -m[qs]; sA[qs][r] = fmaf(sA[qs][r], c_, -m[qs]); }
+        for (int r = 0; r < 16; ++r) sA[qs][r] = fmaf(sA[qs][r], c_, -m[qs]);
       prime_ring();
       do {
         const Tile T4 = gen.next();
@@ -835,13 +813,8 @@ hipError_t launch_any(AttendArgs& a, int d, hipStream_t st) {
   a.nq_tiles = (a.Lc + BM - 1) / BM;
   a.nk_tiles = (a.Lc + BN - 1) / BN;
   const unsigned grid = 8u * (unsigned)((a.BH + 7) / 8) * (unsigned)a.nq_tiles;
-  if (a.exact) {
-    if (d == 128) attend_kernel<128, kQS, FUSED, false><<<grid, 512 / kQS, 0, st>>>(a);
-    else attend_kernel<64, kQS, FUSED, false><<<grid, 512 / kQS, 0, st>>>(a);
-  } else {
-    if (d == 128) attend_kernel<128, kQS, FUSED, true><<<grid, 512 / kQS, 0, st>>>(a);
-    else attend_kernel<64, kQS, FUSED, true><<<grid, 512 / kQS, 0, st>>>(a);
-  }
+  if (d == 128) attend_kernel<128, kQS, FUSED><<<grid, 512 / kQS, 0, st>>>(a);
+  else attend_kernel<64, kQS, FUSED><<<grid, 512 / kQS, 0, st>>>(a);
   return hipGetLastError();
 }
 
@@ -849,9 +822,8 @@ hipError_t launch_any(AttendArgs& a, int d, hipStream_t st) {
 
 hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
                          const void* Vt, const int32_t* block_list, int block_size, int max_blocks_per_row,
-                         int block_list_per_head, int fast_scale, void* Oc, float* lse, hipStream_t st) {
+                         int block_list_per_head, void* Oc, float* lse, hipStream_t st) {
   AttendArgs a;
-  a.exact = fast_scale ? 0 : 1;
   a.block = block_list ? block_size : BM;
   a.bl_head_stride = block_list_per_head ? (long long)((Lc + a.block - 1) / a.block) * max_blocks_per_row : 0;
   a.Q = (const __bf16*)Qc; a.K = (const __bf16*)Kc; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
@@ -871,7 +843,6 @@ hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, con
   AttendArgs a;
   a.k_dev = k_dev;
   a.qs = dm.q; a.ks = dm.kv; a.os = dm.o;
-  a.exact = dm.fast_scale ? 0 : 1;
   a.block = block_list ? block_size : BM;
   a.Q = (const __bf16*)Q; a.K = (const __bf16*)K; a.Vt = (const __bf16*)Vt; a.O = (__bf16*)Oc;
   a.lse = nullptr; a.block_list = block_list; a.max_blocks = max_blocks_per_row;

@@ -39,7 +39,7 @@ struct Strides {
 };
 
 struct Dims {
-  int B, Hq, Hkv, L, d, last_q, pool_w, group_mode, force_first, force_last, block_list_per_head, fast_scale;
+  int B, Hq, Hkv, L, d, last_q, pool_w, group_mode, force_first, force_last, block_list_per_head;
   float scale;
   Strides q, kv, o;            // Q; K and V; O
 };
@@ -98,7 +98,7 @@ hipError_t launch_compress_tiled(const Dims& dm, const void* Q, const void* K, c
 // attend.hip
 hipError_t launch_attend(int B, int Hq, int kv_heads, int Lc, int d, float scale, const void* Qc, const void* Kc,
                          const void* Vt, const int32_t* block_list, int block_size, int max_blocks_per_row,
-                         int block_list_per_head, int fast_scale, void* Oc, float* lse, hipStream_t st);
+                         int block_list_per_head, void* Oc, float* lse, hipStream_t st);
 
 // attend.hip, fused form used by tsa_forward: Q and K are the original tensors, rows are gathered
 // through idx inside the kernel's loads; Vt = tiles of the gathered V (launch_compress_tiled with

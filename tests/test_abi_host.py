@@ -27,8 +27,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_desc_struct_matches_header(lib):
-    assert ctypes.sizeof(tsa.tsa_desc) == 128
-    assert lib.tsa_version() == 8
+    assert ctypes.sizeof(tsa.tsa_desc) == 120
+    assert lib.tsa_version() == 9
 
 
 def test_keep_count_matches_oracle_rule(lib):
@@ -78,8 +78,6 @@ def test_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert "workspace" in tsa.tsa_last_error()
     bad = tsa.make_desc(1, 4, 4, 1024, 64, pool_w=4)
     assert lib.tsa_score(ctypes.byref(bad), fake, fake, fake, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
-    bad = tsa.make_desc(1, 4, 4, 1024, 64, fast_scale=2)
-    assert lib.tsa_attend(ctypes.byref(bad), fake, fake, fake, 16, 4, None, 0, 0, fake, None, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_coverage_budget(dp, fake, 1.5, fake, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_coverage_budget(dp, fake, 0.01, None, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_score(None, fake, fake, fake, fake, 1 << 30, None) == tsa.TSA_ERR_ARG

@@ -203,11 +203,10 @@ def test_compress_keep_all_is_identity(tsa):
     (1, 2, 2, 1, 128), (1, 2, 2, 63, 128), (1, 2, 1, 64, 128), (1, 4, 2, 65, 64), (2, 2, 2, 128, 128),
     (1, 3, 3, 129, 128), (1, 8, 2, 300, 128), (1, 4, 4, 256, 64), (1, 9, 3, 1000, 128), (1, 2, 2, 2049, 64),
 ])
-@pytest.mark.parametrize("fast_scale", [0, 1])
-def test_attend_matches_oracle(tsa, B, Hq, Hk, Lc, d, fast_scale):
+def test_attend_matches_oracle(tsa, B, Hq, Hk, Lc, d):
     r = _rng(400 + Lc + d)
     Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d))
-    desc = tsa.make_desc(B, Hq, Hk, max(Lc, 1), d, 1, fast_scale=fast_scale)
+    desc = tsa.make_desc(B, Hq, Hk, max(Lc, 1), d, 1)
     O = torch.full((B, Hq, Lc, d), 9.0, dtype=torch.bfloat16, device=gu.DEV)
     lse = torch.zeros((B, Hq, Lc), dtype=torch.float32, device=gu.DEV)
     Vd = gu.to_dev(Vb)
@@ -216,48 +215,25 @@ def test_attend_matches_oracle(tsa, B, Hq, Hk, Lc, d, fast_scale):
     assert np.array_equal(gu.from_dev(Vd), Vb)                 # the caller's V is left alone
     want, wlse = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), return_lse=True)
     gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend")
-    # With fast_scale the kernel multiplies Q by scale * log2(e) and rounds it to bf16 before the products:
-    # every scaled logit moves by sum_i k_i * dq_i with |dq_i| <= 2^-9 |scale * q_i|, about 1.1e-3 rms
-    # for unit-variance rows of either head size, and the log-sum-exp is a weighted mean of the logits:
-    # the bound is five times that rms.  By default the logits only carry fp32 rounding.
-    assert np.abs(lse.cpu().numpy() - wlse).max() < (6e-3 if fast_scale else 2e-3)
+    assert np.abs(lse.cpu().numpy() - wlse).max() < 2e-3
     # row 0 attends to a single key: the output is v_0 exactly
     g = Hq // Hk
     for h in range(Hq):
         assert np.array_equal(gu.from_dev(O)[0, h, 0], Vb[0, h // g, 0])
 
 
-@pytest.mark.parametrize("fast_scale", [0, 1])
-def test_attend_large_logits_and_scale(tsa, fast_scale):
+def test_attend_large_logits_and_scale(tsa):
     r = _rng(21)
     B, H, Lc, d = 1, 2, 500, 128
     Qb, Kb, Vb = gu.rand_bits(r, (B, H, Lc, d), 4.0), gu.rand_bits(r, (B, H, Lc, d), 4.0), gu.rand_bits(r, (B, H, Lc, d))
-    # logits of several hundred: the running max must hold
-    desc = tsa.make_desc(B, H, H, Lc, d, 1, scale=0.2, fast_scale=fast_scale)
+    desc = tsa.make_desc(B, H, H, Lc, d, 1, scale=0.2)        # logits of several hundred: the running max must hold
     O = torch.empty((B, H, Lc, d), dtype=torch.bfloat16, device=gu.DEV)
     tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, H, O, tsa.alloc_attend_workspace(desc, Lc, H, gu.DEV))
-    if not fast_scale:   # products scaled in fp32: the plain oracle at the plain bars
-        want = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), scale=0.2)
-        gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(large logits)")
-        return
-    # The stated arithmetic of fast_scale rounds Q * (scale * log2 e) to bf16 before the products.  With
-    # logits this large that rounding alone moves near-ties between keys, so the running-max logic
-    # is checked against the oracle on exactly those rounded queries (logits then in log2 units) ...
-    c32 = np.float32(0.2) * np.float32(1.4426950408889634)
-    Qs = orc.f64_to_bf16((orc.bf16_to_f64(Qb).astype(np.float32) * c32).astype(np.float64))
-    want = orc.attend(orc.bf16_to_f64(Qs), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), scale=float(np.log(2.0)))
-    gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(large logits, fast scale)")
-    # ... and against the oracle on the queries as given, within what the rounding explains: each logit
-    # moves by about 2^-9 / sqrt(3) * 0.2 * 16 * sqrt(128) = 0.04 rms, a few near-ties shift weight
-    # between two value rows (max), the bulk of the rows does not notice (mean).
-    plain = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), scale=0.2)
-    err = np.abs(orc.bf16_to_f64(gu.from_dev(O)) - plain)
-    print("large logits vs unrounded queries: max-abs %.4g mean-abs %.4g" % (err.max(), err.mean()))
-    assert err.max() <= 0.35 and err.mean() <= 1e-2
+    want = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), scale=0.2)
+    gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(large logits)")
 
 
-@pytest.mark.parametrize("fast_scale", [0, 1])
-def test_attend_logits_growing_along_the_keys(tsa, fast_scale):
+def test_attend_logits_growing_along_the_keys(tsa):
     """Keys grow along the sequence (logit of key c about 0.066 c nats, 190 log2 units over the row):
     the running max is raised every tile or two, in the middle of the pipelined iterations, where the
     half tile that waits for its exponentials has to be shifted together with the accumulator."""
@@ -267,15 +243,13 @@ def test_attend_logits_growing_along_the_keys(tsa, fast_scale):
     q = 6.0 * u + 0.3 * r.standard_normal((B, H, Lc, d))
     k = (np.arange(Lc)[None, None, :, None] / 8.0) * u + 0.3 * r.standard_normal((B, H, Lc, d))
     Qb, Kb, Vb = orc.f64_to_bf16(q), orc.f64_to_bf16(k), gu.rand_bits(r, (B, H, Lc, d))
-    desc = tsa.make_desc(B, H, H, Lc, d, 1, fast_scale=fast_scale)
+    desc = tsa.make_desc(B, H, H, Lc, d, 1)
     O = torch.empty((B, H, Lc, d), dtype=torch.bfloat16, device=gu.DEV)
     lse = torch.zeros((B, H, Lc), dtype=torch.float32, device=gu.DEV)
     tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, H, O, tsa.alloc_attend_workspace(desc, Lc, H, gu.DEV), lse)
     want, wlse = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), return_lse=True)
     gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(growing logits)")
-    # the log-sum-exp follows the largest logits (up to 130 nats here), which the rounding of the scaled
-    # queries (fast_scale) moves by up to 2^-9 of their size
-    assert np.abs(lse.cpu().numpy() - wlse).max() < (130 * 2.0 ** -9 + 6e-3 if fast_scale else 2e-3)
+    assert np.abs(lse.cpu().numpy() - wlse).max() < 2e-3
 
 
 # (3000, 1024): long stretches of pipelined iterations between the sink block, the window's first
@@ -304,15 +278,14 @@ def test_attend_block_list(tsa, Lc, window, Bs):
     (2, 2, 257, 128, 64, 257, 0, "direction"),     # keep everything: dense causal attention
     (2, 1, 200, 64, 8, 1, 0, "norm"),              # keep a single token
 ])
-@pytest.mark.parametrize("fast_scale", [0, 1])
-def test_forward_small(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant, fast_scale):
+def test_forward_small(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant):
     from paper_2602_03216_amd import inputs as gen
     from tests.margin import enforce_margin
     cfg = dict(id=90, name="small", B=1, Hq=Hq, Hkv=Hkv, L=L, d=d, last_q=Lq, plant=plant, n_plant=20, norm_factor=3.0,
                frac_plant=0.1, boost=4.0, sink_boost=6.0, n_sink=4, zipf_a=1.2)
     inp = gen.make_inputs(cfg, seed=600 + L)
     enforce_margin(inp, [k], group_mode)            # the k-th / (k+1)-th scores are separated: one right answer
-    desc = tsa.make_desc(1, Hq, Hkv, L, d, Lq, group_mode=group_mode, fast_scale=fast_scale)
+    desc = tsa.make_desc(1, Hq, Hkv, L, d, Lq, group_mode=group_mode)
     Hs = Hkv if group_mode else Hq
     O = torch.full((1, Hq, L, d), 3.0, dtype=torch.bfloat16, device=gu.DEV)
     idx = torch.zeros((1, Hs, k), dtype=torch.int32, device=gu.DEV)
@@ -387,8 +360,7 @@ def _random_forward_cases(n, seed):
 @pytest.mark.parametrize("Hq,Hkv,L,d,Lq,k,group_mode,plant,pool_w", _random_forward_cases(40, 20260203))
 def test_forward_random_shapes(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant, pool_w):
     """Seeded sweep over ragged shapes, head groupings, window lengths, counts, both selection modes and
-    pooling widths: index sets bit-exact, outputs within the bars, zero rows exact.  (Default scaling: with
-    fast_scale the short rows with planted key norms of this sweep move by up to 8e-2, see tsa_attend.)"""
+    pooling widths: index sets bit-exact, outputs within the bars, zero rows exact."""
     from paper_2602_03216_amd import inputs as gen
     from tests.margin import boundary_margin, enforce_margin, RHO
     cfg = dict(id=91, name="random", B=1, Hq=Hq, Hkv=Hkv, L=L, d=d, last_q=Lq, plant=plant, n_plant=min(20, max(1, L // 4)),
@@ -421,8 +393,7 @@ def test_forward_random_shapes(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant, poo
     (3, 2, 1, 777, 64, 200, 0, True),
     (2, 4, 2, 520, 128, 1, 0, False),
 ])
-@pytest.mark.parametrize("fast_scale", [0, 1])
-def test_fused_path_equals_the_separate_calls(tsa, B, Hq, Hkv, L, d, k, group_mode, with_blocks, fast_scale):
+def test_fused_path_equals_the_separate_calls(tsa, B, Hq, Hkv, L, d, k, group_mode, with_blocks):
     """tsa_forward / tsa_compress_v_tiles + tsa_attend_fused against tsa_score -> tsa_select ->
     tsa_compress -> tsa_attend -> tsa_decompress on the same inputs: gather and scatter are copies
     and the arithmetic is the same, so every output must match bit for bit (the separate calls are
@@ -430,7 +401,7 @@ def test_fused_path_equals_the_separate_calls(tsa, B, Hq, Hkv, L, d, k, group_mo
     r = _rng(900 + L)
     Lq = 64
     Q, K, V = (gu.to_dev(gu.rand_bits(r, (B, h, L, d))) for h in (Hq, Hkv, Hkv))
-    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq, group_mode=group_mode, fast_scale=fast_scale)
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq, group_mode=group_mode)
     Hs = Hkv if group_mode else Hq
     ws = _ws(tsa, desc, k)
     bl = bl_kw = None
