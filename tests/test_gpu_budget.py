@@ -165,3 +165,13 @@ def test_forward_dynamic_against_the_oracle(tsa):
     ref = orc.forward(inp.Q, inp.K, inp.V, k, Lq)
     assert np.array_equal(idx[:, :, :k].cpu().numpy(), ref["idx"])
     gu.assert_output_close(gu.from_dev(O), ref["O"], "forward_dynamic")
+
+
+def test_forward_dynamic_random_sweep(tsa):
+    """Seeded sweep: 30 random shapes, thresholds, capacities, both selection modes, pooled scores."""
+    r = np.random.Generator(np.random.PCG64(51))
+    for i in range(30):
+        B = int(r.choice([1, 2, 3])); d = int(r.choice([64, 128])); Hkv = int(r.choice([1, 2])); Hq = Hkv * int(r.choice([1, 2, 4]))
+        L = int(r.integers(1, 3000)); tau = float(r.choice([0.0, 0.003, 0.02, 0.1, 0.5, 0.95, 1.0]))
+        k_max = int(r.choice([L, L, max(1, L // 2), max(1, L // 7)]))
+        _dynamic_case(tsa, B, Hq, Hkv, L, d, tau, k_max, int(r.integers(0, 2)), seed=5000 + i)

@@ -298,6 +298,33 @@ def test_forward_small(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant):
     assert not gu.from_dev(O)[np.repeat(~sel, Hq // Hs, axis=1)].any()
 
 
+def test_attend_random_sweep(tsa):
+    """Seeded sweep: 40 random attention problems (1 to 2600 rows, both head sizes, grouped heads, one or
+    two batch entries) with no block list, a sink + window list or per-head vertical + slash lists, at
+    the three block sizes: outputs within the bars of the oracle."""
+    from paper_2602_03216_amd import inputs as gen
+    r = _rng(41)
+    for i in range(40):
+        d = int(r.choice([64, 128])); Hk = int(r.choice([1, 2, 3])); Hq = Hk * int(r.choice([1, 2, 4])); B = int(r.choice([1, 1, 2]))
+        Lc = int(r.integers(1, 2600)); mode = i % 3; Bs = int(r.choice([64, 128, 256]))
+        Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d))
+        kw, okw, per_head = {}, {}, 0
+        if mode == 1:
+            bl = orc.lambda_block_list(Lc, Bs, int(r.choice([64, 256, 700, 5000])), int(r.choice([1, 2])))
+        elif mode == 2:
+            bl = gen.vertical_slash_block_lists(B, Hq, (Lc + Bs - 1) // Bs, int(r.integers(1 << 30)), n_vertical=int(r.integers(0, 4)),
+                                                slash_blocks=int(r.integers(0, 4)), n_extra=int(r.integers(0, 3)))
+            per_head = 1
+        if mode:
+            kw = dict(block_list=torch.from_numpy(np.ascontiguousarray(bl)).to(gu.DEV), block_size=Bs, max_blocks_per_row=bl.shape[-1])
+            okw = dict(block_list=bl, block_size=Bs)
+        desc = tsa.make_desc(B, Hq, Hk, Lc, d, 1, block_list_per_head=per_head)
+        O = torch.full((B, Hq, Lc, d), 9.0, dtype=torch.bfloat16, device=gu.DEV)
+        tsa.tsa_attend(desc, gu.to_dev(Qb), gu.to_dev(Kb), gu.to_dev(Vb), Lc, Hk, O, tsa.alloc_attend_workspace(desc, Lc, Hk, gu.DEV), **kw)
+        want = orc.attend(orc.bf16_to_f64(Qb), orc.bf16_to_f64(Kb), orc.bf16_to_f64(Vb), **okw)
+        gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend %s" % ((B, Hq, Hk, Lc, d, mode, Bs),))
+
+
 def test_select_and_budget_random_sweep(tsa):
     """Seeded sweep: 60 random shapes (1 to 140000 tokens, one to three batch entries, both selection
     modes, forced tokens) on four kinds of scores (uniform, a handful of distinct values, signed zeros
