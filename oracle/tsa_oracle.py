@@ -8,15 +8,15 @@ this module imports nothing from the product package.
 Everything is numpy float64 on the exact values of the bf16 inputs.  Each
 function follows one passage of the paper:
 
-  score       Algorithm 1, steps "attention scores using recent queries" and
-              "token-level scores per head" (Section 2.3, Dynamic Token Coverage)
+  score       Algorithm 1, its first two steps: proxy attention of the most recent
+              queries, then the per-head column sums (Section 2.3, Dynamic Token Coverage)
   pool        the pooling(.) of the same step (the paper does not give the
               kernel; reading: average pooling, stride 1, zero padding)
-  coverage_budget  Algorithm 1, cross-head aggregation, ascending sort, cumulative-mass
-              threshold tau -> k_sparse, k_keep (the paper's dynamic budget)
-  keep_count  the fixed token-sparsity ratio of the "Dynamic Sparsity vs. Fixed
-              Sparsity" comparison (Table 4): a constant fraction of tokens kept
-  select      Algorithm 1, "Head-wise top-k_keep token selection"
+  coverage_budget  Algorithm 1, its budget steps: cross-head sum and normalisation, ascending
+              order, cumulative-mass threshold tau -> k_sparse, k_keep (the dynamic budget)
+  keep_count  the fixed token-sparsity ratio the paper compares its dynamic budget
+              with (Table 4): a constant fraction of tokens kept
+  select      Algorithm 1, its last step: per-head top-k_keep selection
   compress    Section 2.2, Stage 1 (gather rows of Q, K, V by S_h)
   attend      Section 2.2, Stage 1 last sentence: attention on the compressed
               tensors; causal, as for the decoder-only models of Section 3.1
@@ -183,22 +183,16 @@ def keep_count(L: int, tau: float) -> int:
 
 
 def coverage_budget(s: np.ndarray, tau_cov: float) -> np.ndarray:
-    """Dynamic Token Coverage budget, Algorithm 1 steps "aggregate and normalize token scores
-    across heads", "sort tokens by ascending importance" and "determine the number of sparse
-    token": s_l = sum_h s_h / sum_t sum_h s_h[t]; I = argsort(s_l); k_sparse = the smallest k in
-    {0..L} whose k least important tokens carry a cumulative mass >= tau_cov; k_keep = L - k_sparse
-    (at least 1).  s [B,Hq,L]; one k_keep per batch element, int32 [B].
-
-    The head sum is taken in float32, in head order (the precision the HIP kernel decides the
-    order of near-equal tokens in); normalisation and the cumulative mass are float64."""
-    s = np.asarray(s)
+    """Dynamic Token Coverage budget, the budget steps of Algorithm 1 (Section 2.3): the scores
+    are summed over the heads and normalised to total mass one, s_l = sum_h s_h / sum_t sum_h s_h[t];
+    the tokens are put in ascending order of s_l; k_sparse is the smallest k in {0..L} whose k least
+    important tokens carry a cumulative mass >= tau_cov; k_keep = L - k_sparse (at least 1).
+    s [B,Hq,L]; one k_keep per batch element, int32 [B].  Everything in float64."""
+    s = np.asarray(s, dtype=np.float64)
     B, Hq, L = s.shape
     out = np.empty(B, dtype=np.int32)
     for b in range(B):
-        sl32 = np.zeros(L, dtype=np.float32)
-        for h in range(Hq):
-            sl32 = sl32 + s[b, h].astype(np.float32)
-        sl = sl32.astype(np.float64)
+        sl = s[b].sum(axis=0)
         sl = sl / sl.sum()
         order = np.argsort(sl, kind="stable")
         cum = np.cumsum(sl[order])

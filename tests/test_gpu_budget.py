@@ -1,6 +1,9 @@
 """GPU parity of the Dynamic Token Coverage budget (Algorithm 1: cross-head aggregation, ascending
-order, cumulative-mass threshold) against the oracle, through the C ABI.  k_keep is an integer:
-it must match exactly.  Both sides form the head sum in float32 in head order; masses are float64."""
+order, cumulative-mass threshold) against the oracle, through the C ABI.  k_keep is an integer.
+The oracle works in float64 throughout; the library adds the heads in float32.  Where the float32
+head sums are exact (scores that are multiples of 2^-20 below 1, at most 16 heads) the count must
+be equal; on general scores it must lie between the oracle's counts at tau (1 +- eps), eps being
+the bound on the relative error of a float32 sum of Hq non-negative terms and of the total."""
 import numpy as np
 import pytest
 import torch
@@ -19,6 +22,19 @@ def tsa():
     return binding
 
 
+def _bracket(s_np, tau):
+    """The oracle's counts at tau (1 + eps) and tau (1 - eps): any count in between is a correct
+    answer for scores known to a relative eps.  eps: Hq - 1 float32 additions per token, 2^-24
+    each, doubled for the ratio to the total."""
+    eps = 2.0 * s_np.shape[1] * 2.0 ** -24
+    return orc.coverage_budget(s_np, min(1.0, tau * (1 + eps))), orc.coverage_budget(s_np, tau * (1 - eps))
+
+
+def _assert_in_bracket(got, s_np, tau, what=""):
+    lo, hi = _bracket(s_np, tau)
+    assert np.all(lo <= got) and np.all(got <= hi), (what, tau, lo.tolist(), np.asarray(got).tolist(), hi.tolist())
+
+
 def _budget(tsa, s_np, tau):
     B, Hq, L = s_np.shape
     desc = tsa.make_desc(B, Hq, Hq, L, 128, min(64, L))
@@ -33,9 +49,11 @@ def _budget(tsa, s_np, tau):
 def test_budget_random_scores(tsa, B, Hq, L):
     r = np.random.Generator(np.random.PCG64(700 + L))
     s = (r.random((B, Hq, L)) ** 4).astype(np.float32)            # long tail of small scores
+    q = 2.0 ** (24 - int(np.ceil(np.log2(max(Hq, 2)))))            # Hq values below 1 on this grid add up exactly in float32
+    sq = (np.floor(s * q) / q).astype(np.float32)
     for tau in (0.0, 1e-4, 0.005, 0.01, 0.2, 0.9, 1.0):
-        got = _budget(tsa, s, tau)
-        want = orc.coverage_budget(s, tau)
+        _assert_in_bracket(_budget(tsa, s, tau), s, tau)
+        got, want = _budget(tsa, sq, tau), orc.coverage_budget(sq, tau)
         assert np.array_equal(got, want), (tau, got, want)
 
 
@@ -70,7 +88,7 @@ def test_budget_on_scored_workload_then_forward(tsa):
         tsa.tsa_coverage_budget(desc, s, tau, kk, ws)
         torch.cuda.synchronize()
         k = int(kk.item())
-        assert k == int(orc.coverage_budget(s_np, tau)[0])
+        _assert_in_bracket(np.array([k]), s_np, tau, "scored workload")
         assert 1 <= k < L
         O = torch.empty_like(Q)
         idx = torch.empty((1, cfg["Hq"], k), dtype=torch.int32, device=gu.DEV)
@@ -83,9 +101,9 @@ def test_budget_on_scored_workload_then_forward(tsa):
 
 
 def _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed, window=0):
-    """tsa_forward_dynamic against (a) the oracle's budget on the library's own scores: the count is an
-    integer decided by fp64 masses of the same fp32 numbers, so it must match exactly; (b) tsa_forward
-    with that count, batch entry by batch entry: the same kernels on the same data, bit for bit."""
+    """tsa_forward_dynamic against (a) the oracle's budget on the library's own scores: the count must
+    lie in the oracle's bracket for those scores; (b) tsa_forward with that count, batch entry by batch
+    entry: the same kernels on the same data, bit for bit."""
     r = np.random.Generator(np.random.PCG64(seed))
     Lq = min(64, L)
     Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, L, d)), gu.rand_bits(r, (B, Hkv, L, d), 1.5), gu.rand_bits(r, (B, Hkv, L, d))
@@ -94,7 +112,7 @@ def _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed, windo
     Hs = Hkv if group_mode else Hq
     s = torch.empty((B, Hq, L), dtype=torch.float32, device=gu.DEV)
     tsa.tsa_score(desc, Q, K, s, tsa.alloc_workspace(desc, 1, gu.DEV))
-    want_k = np.minimum(orc.coverage_budget(s.cpu().numpy(), tau_cov), k_max)
+    s_np = s.cpu().numpy()
     O = torch.full((B, Hq, L, d), 7.0, dtype=torch.bfloat16, device=gu.DEV)
     kk = torch.full((B,), -3, dtype=torch.int32, device=gu.DEV)
     idx = torch.full((B, Hs, k_max), -9, dtype=torch.int32, device=gu.DEV)
@@ -106,7 +124,8 @@ def _dynamic_case(tsa, B, Hq, Hkv, L, d, tau_cov, k_max, group_mode, seed, windo
                             k_keep_out=kk, idx_out=idx, **kw)
     torch.cuda.synchronize()
     got_k = kk.cpu().numpy()
-    assert np.array_equal(got_k, want_k), (got_k, want_k)
+    lo, hi = _bracket(s_np, tau_cov)
+    assert np.all(np.minimum(lo, k_max) <= got_k) and np.all(got_k <= np.minimum(hi, k_max)), (lo, got_k, hi, k_max)
     for b in range(B):
         k = int(got_k[b])
         d1 = tsa.make_desc(1, Hq, Hkv, L, d, Lq, group_mode=group_mode)
@@ -137,19 +156,23 @@ def test_forward_dynamic_equals_budget_then_forward(tsa, B, Hq, Hkv, L, d, tau_c
 
 def test_forward_dynamic_against_the_oracle(tsa):
     """The oracle end to end: its own scores, its own budget, its own forward with that count.  The
-    margin of the count is checked first (the cumulative mass must not cross tau_cov within the
-    library's score error of 3e-5), then index sets bit-exact and outputs within the bars."""
+    inputs get a margin at the k-th / (k+1)-th score of every head, and tau_cov is put halfway between
+    two consecutive values of the oracle's cumulative mass, so that the count has a margin too (half a
+    token's mass, some ten times the effect of the library's score error of 3e-5): the count must be
+    equal, the index sets bit-exact and the outputs within the bars."""
     inp = gen.make_inputs(3, L=4096)
     cfg = inp.cfg
     B, Hq, Hkv, L, d, Lq = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"]
     s_ref = orc.score(orc.bf16_to_f64(inp.Q), orc.bf16_to_f64(inp.K), Lq)
-    tau_cov = 0.01
-    k_lo, k_hi = orc.coverage_budget(s_ref, tau_cov * (1 - 1e-3))[0], orc.coverage_budget(s_ref, tau_cov * (1 + 1e-3))[0]
-    k = int(orc.coverage_budget(s_ref, tau_cov)[0])
+    k = int(orc.coverage_budget(s_ref, 0.01)[0])
     from tests.margin import enforce_margin
-    enforce_margin(inp, [k], 0)
-    s_ref = orc.score(orc.bf16_to_f64(inp.Q), orc.bf16_to_f64(inp.K), Lq)
-    k = int(orc.coverage_budget(s_ref, tau_cov)[0])
+    s_ref, _ = enforce_margin(inp, [k], 0)
+    sl = np.sort(s_ref[0].sum(axis=0))
+    cum = np.cumsum(sl / sl.sum())
+    k_sparse = L - k
+    tau_cov = 0.5 * (cum[k_sparse - 2] + cum[k_sparse - 1])
+    assert int(orc.coverage_budget(s_ref, tau_cov)[0]) == k
+    assert (cum[k_sparse - 1] - cum[k_sparse - 2]) / tau_cov > 20 * 3e-5
     desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq)
     Q, K, V = gu.to_dev(inp.Q), gu.to_dev(inp.K), gu.to_dev(inp.V)
     O = torch.empty((B, Hq, L, d), dtype=torch.bfloat16, device=gu.DEV)
@@ -158,10 +181,7 @@ def test_forward_dynamic_against_the_oracle(tsa):
     tsa.tsa_forward_dynamic(desc, Q, K, V, tau_cov, L, O, tsa.alloc_forward_dynamic_workspace(desc, L, gu.DEV),
                             k_keep_out=kk, idx_out=idx)
     torch.cuda.synchronize()
-    got_k = int(kk[0].item())
-    assert k_hi <= got_k <= k_lo, (k_hi, got_k, k_lo)
-    if got_k != k:
-        pytest.skip("the count sits on a rounding boundary of the scores (%d vs %d)" % (got_k, k))
+    assert int(kk[0].item()) == k
     ref = orc.forward(inp.Q, inp.K, inp.V, k, Lq)
     assert np.array_equal(idx[:, :, :k].cpu().numpy(), ref["idx"])
     gu.assert_output_close(gu.from_dev(O), ref["O"], "forward_dynamic")

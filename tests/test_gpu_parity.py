@@ -328,7 +328,8 @@ def test_attend_random_sweep(tsa):
 def test_select_and_budget_random_sweep(tsa):
     """Seeded sweep: 60 random shapes (1 to 140000 tokens, one to three batch entries, both selection
     modes, forced tokens) on four kinds of scores (uniform, a handful of distinct values, signed zeros
-    only, a long tail with a repeated value): index sets, inverse maps and budgets bit-exact."""
+    only, a long tail with a repeated value), quantised so that float32 sums over heads are exact: index
+    sets, inverse maps and budgets bit-exact against the float64 oracle."""
     r = _rng(31)
     for i in range(60):
         B = int(r.choice([1, 1, 2, 3])); Hkv = int(r.choice([1, 2, 4])); Hq = Hkv * int(r.choice([1, 2, 4])); gm = int(r.integers(0, 2))
@@ -346,19 +347,17 @@ def test_select_and_budget_random_sweep(tsa):
         else:
             s = (r.random((B, Hq, L)) ** 8).astype(np.float32)
             s[..., ::7] = s[..., 0:1]
+        # multiples of 2^-20 below 1, at most 16 heads: the float32 sums over a group and over all
+        # heads (which the library forms) are exact, so the float64 oracle must give the same answer
+        s = (np.floor(s * 2.0 ** 20) / 2.0 ** 20).astype(np.float32)
         desc = tsa.make_desc(B, Hq, Hkv, L, 128, min(64, L), group_mode=gm, force_first=ff, force_last=fl)
         Hs = Hkv if gm else Hq
         sd = torch.from_numpy(s).to(gu.DEV)
         idx = torch.full((B, Hs, k), -7, dtype=torch.int32, device=gu.DEV)
         inv = torch.full((B, Hs, L), -7, dtype=torch.int32, device=gu.DEV)
         tsa.tsa_select(desc, sd, k, idx, inv, _ws(tsa, desc, k))
-        sel = s
-        if gm:          # the library sums the heads of a group in float32, in head order
-            g = Hq // Hkv
-            sel = np.zeros((B, Hkv, L), dtype=np.float32)
-            for j in range(g):
-                sel = (sel + s.reshape(B, Hkv, g, L)[:, :, j]).astype(np.float32)
-        widx, winv = orc.select(sel.astype(np.float64), k, force_first=ff, force_last=fl)
+        sel = orc.group_scores(s.astype(np.float64), Hq // Hkv) if gm else s.astype(np.float64)
+        widx, winv = orc.select(sel, k, force_first=ff, force_last=fl)
         what = (B, Hq, Hkv, gm, L, k, ff, fl, kind)
         assert np.array_equal(idx.cpu().numpy(), widx), what
         assert np.array_equal(inv.cpu().numpy(), winv), what

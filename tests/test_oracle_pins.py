@@ -261,6 +261,22 @@ def test_coverage_budget_hand_cases_and_brute_force():
             assert orc.coverage_budget(s, tau).tolist() == _budget_brute(s.tolist(), tau)
 
 
+def test_coverage_budget_sums_the_heads_exactly():
+    # head sums [1 + 2^-30, 1, 1]: the term 2^-30 survives only in a sum wider than float32.  With
+    # tau = 1/3 the lightest token alone carries 1 / (3 + 2^-30) < 1/3, so two tokens are needed and one
+    # is kept; a float32 head sum would see three equal tokens, reach 1/3 with one and keep two.
+    s = np.array([[[1.0, 1.0, 1.0], [2.0 ** -30, 0.0, 0.0]]])
+    assert _budget_brute(s.tolist(), 1 / 3) == [1]
+    assert orc.coverage_budget(s, 1 / 3)[0] == 1
+    assert orc.coverage_budget(s.astype(np.float32), 1 / 3)[0] == 1        # float32 INPUT, sum still exact
+    # non-dyadic random scores against exact rational arithmetic (tau away from any cumulative value)
+    r = _rng(77)
+    for trial in range(10):
+        s = r.random((1, 5, 30))
+        for tau in (0.013, 0.21, 0.66):
+            assert orc.coverage_budget(s, tau).tolist() == _budget_brute(s.tolist(), tau)
+
+
 def test_coverage_budget_long_tail_prunes_the_tail():
     # a few heavy tokens and a long tail of mass 0.4 %: tau = 0.5 % removes exactly the tail
     L = 1000
