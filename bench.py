@@ -114,6 +114,11 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
         }
         kk = torch.zeros(B, dtype=torch.int32, device=dev)
         parts["budget"] = lambda: tsa.tsa_coverage_budget(desc, scores, 0.005, kk, ws)   # the paper's tau for this model family
+        # the same layer with one index set per KV group chosen from the group's summed scores
+        # (compacted K, V stay grouped: attention reads each gathered K/V row for g query heads)
+        desc_g = tsa.make_desc(B, Hq, Hkv, L, d, Lq, group_mode=1)
+        ws_g = tsa.alloc_workspace(desc_g, k, dev)
+        parts["forward_group_sets"] = lambda: tsa.tsa_forward(desc_g, Q, K, V, k, O, ws_g)
         t = {}
         for name, fn in parts.items():
             fn()
@@ -138,14 +143,19 @@ def bench_workload(tsa, torch, gen, cfg_id, taus, steps, warmup, dense_iters, pa
             "select_gbs": w["select_bytes"] / t["select"] / 1e6,
             "compress_gbs": w["compress_bytes"] / t["compress"] / 1e6,
             "decompress_gbs": w["decompress_bytes"] / t["decompress"] / 1e6,
+            # what the separate entry points would add around attention, and what tsa_forward itself
+            # pays beside its attention launch (scoring, selection, the V gather into tiles)
             "overhead_frac_of_forward": (t["score"] + t["select"] + t["compress"] + t["decompress"]) / t_fwd,
+            "overhead_fused_ms": t["score"] + t["select"] + t["v_tiles"],
+            "overhead_fused_frac_of_forward": (t["score"] + t["select"] + t["v_tiles"]) / t_fwd,
+            "forward_group_sets_ms": t["forward_group_sets"],
         }
         for nm in ("score", "select", "compress", "decompress"):
             rec[nm + "_frac_hbm_peak"] = rec[nm + "_gbs"] / HBM_PEAK_GBS
         if tau == taus[0] and k < L:
             rec["dynamic_coverage"] = bench_dynamic(tsa, torch, desc, Q, K, V, O, scores, kk, ws, k, steps, warmup, t_fwd)
         out["per_tau"][str(tau)] = rec
-        del ws, scores, idx, inv, Qc, Kc, Vc, Oc, vt
+        del ws, ws_g, scores, idx, inv, Qc, Kc, Vc, Oc, vt
     return out, inp
 
 
@@ -320,12 +330,19 @@ def main():
     torch.cuda.set_device(0)
 
     # a plain device-to-device copy of known size (1 GiB read, 1 GiB written): the reference that
-    # rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by when HBM traffic is profiled
+    # rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by when HBM traffic is profiled; timed,
+    # next to the library's own streaming copy, as the rate a pure mover reaches on this chip
     src = torch.ones(1 << 28, dtype=torch.int32, device="cuda:0")
     dst = torch.empty_like(src)
     for _ in range(2):
         dst.copy_(src)
     torch.cuda.synchronize()
+    gib2 = 2.0 * src.numel() * 4
+    hbm_copy = {"bytes_moved": gib2, "nominal_peak_gbs": HBM_PEAK_GBS,
+                "torch_copy_gbs": gib2 / _events_ms(lambda: dst.copy_(src), 5, torch) / 1e6}
+    tsa.tsa_copy_probe(src, dst)
+    torch.cuda.synchronize()
+    hbm_copy["own_streaming_copy_gbs"] = gib2 / _events_ms(lambda: tsa.tsa_copy_probe(src, dst), 5, torch) / 1e6
     del src, dst
 
     head_tau = 0.75
@@ -336,6 +353,8 @@ def main():
         r32, _ = bench_workload(tsa, torch, gen, 3, gen.CONFIGS[3]["taus"], args.steps, args.warmup, dense_iters=5, part_iters=10)
         detail["gqa_32k"] = r32
         detail["stack_64k"] = bench_stack(tsa, torch, gen, args.steps, args.warmup)
+        r8, _ = bench_workload(tsa, torch, gen, 2, gen.CONFIGS[2]["taus"], args.steps, args.warmup, dense_iters=10, part_iters=20)
+        detail["mha_8k"] = r8
     head = r128["per_tau"][str(head_tau)]
     cfg = inp128.cfg
     import numpy as np
@@ -352,6 +371,7 @@ def main():
         "speedup_attend_vs_own_dense": head["speedup_attend_vs_dense"],
         "ideal_attend_speedup": head["ideal_attend_speedup"],
         "dense_ms": r128["dense_ms"],
+        "hbm_copy": hbm_copy,
         "roofline": {"kernel": "attend_kernel<128, 1, true> (tsa_attend_fused: the attention launch of tsa_forward; template arguments: d, query sub-tiles per wavefront, fused gather/scatter)",
                      "bound": "mfma", "achieved": head["attend_fused_tflops"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": head["attend_fused_frac_mfma_peak"],

@@ -53,7 +53,10 @@ typedef struct tsa_desc {
   int32_t group_mode;   /* 0: every query head selects its own S_h; 1: the g heads of a KV group share
                            one set chosen from the sum of their scores */
   int32_t force_first;  /* tokens t < force_first are always kept (score treated as +inf); default 0 */
-  int32_t force_last;   /* tokens t >= L - force_last are always kept; default 0 */
+  int32_t force_last;   /* tokens t >= L - force_last are always kept; default 0.  Selection needs
+                           force_first + force_last <= k_keep (TSA_ERR_ARG otherwise); with a count decided
+                           on the device the count is raised to force_first + force_last where the budget
+                           asks for fewer */
   float   scale;        /* softmax scale; 0 means 1/sqrt(d) */
   int32_t block_list_per_head; /* 0: one block list shared by all heads; 1: one list per (b, h),
                                   block_list is [B,Hq,ceil(Lc/block_size),max_blocks_per_row] (block-sparse
@@ -103,8 +106,8 @@ int tsa_score(const tsa_desc* desc, const void* Q, const void* K, float* scores,
  * tsa_score_queries: as tsa_score, but the scoring queries are the rows of Qsel [B,Hq,n,d] bf16 (device),
  *   query j sitting at position qpos[j]: s[b,h,t] = sum_j softmax_t(scale Qsel[b,h,j].k_t) over keys
  *   t <= qpos[j].  qpos: HOST array of n ints in [0, L), ascending (it travels in the kernel
- *   arguments); n must equal desc->last_q (which sizes the workspace).  tsa_score is the case
- *   Qsel = Q[:, :, L-n:], qpos = L-n .. L-1.
+ *   arguments); 1 <= n <= 128 (desc->last_q is not used);  ws: tsa_score_queries_workspace_bytes(desc, n)
+ *   bytes.  tsa_score is the case Qsel = Q[:, :, L-n:], qpos = L-n .. L-1.
  * tsa_gather_queries: Qsel[b,h,j,:] = Q[b,h,qpos[j],:] -- the rows of randomly selected queries; the
  *   caller draws the positions (seeded, sorted) and passes them in, 1 <= n <= 128.
  * tsa_pool_queries: query-only pooling: the L rows of every head are cut into n_pool contiguous
@@ -113,6 +116,7 @@ int tsa_score(const tsa_desc* desc, const void* Q, const void* K, float* scores,
  *   receives the last row of each segment, the position a pooled query scores from.  The paper
  *   does not give the pooling window or the causal treatment: n_pool = 1 is a single mean query
  *   that sees every key. */
+size_t tsa_score_queries_workspace_bytes(const tsa_desc* desc, int32_t n);
 int tsa_score_queries(const tsa_desc* desc, const void* Qsel, const int32_t* qpos, int32_t n, const void* K,
                       float* scores, void* ws, size_t ws_bytes, void* stream);
 int tsa_gather_queries(const tsa_desc* desc, const void* Q, const int32_t* qpos, int32_t n, void* Qsel, void* stream);
@@ -120,12 +124,14 @@ size_t tsa_pool_queries_workspace_bytes(const tsa_desc* desc, int32_t n_pool);
 int tsa_pool_queries(const tsa_desc* desc, const void* Q, int32_t n_pool, void* Qsel, int32_t* qpos,
                      void* ws, size_t ws_bytes, void* stream);
 
-/* Dynamic Token Coverage budget -- Algorithm 1, steps "aggregate and normalize token scores across
- * heads", "sort tokens by ascending importance" and "determine the number of sparse token":
+/* Dynamic Token Coverage budget -- Algorithm 1, its budget steps (Section 2.3): cross-head sum of the
+ * token scores, normalisation, ascending order, cumulative-mass threshold:
  * s_l[t] = sum_h scores[b,h,t] (fp32, head order), normalised by its total over t; k_sparse is the
  * smallest k in {0..L} such that the k least important tokens carry a cumulative mass >= tau_cov;
  * k_keep[b] = L - k_sparse, at least 1.  The result stays on the device; a caller that sizes buffers
  * with it reads it back after synchronising the stream, then calls tsa_select with it.
+ * The masses are accumulated exactly (integer sums of significands), so the count does not depend on
+ * the order in which the hardware adds them: repeated calls give the same count.
  *   scores [B,Hq,L] fp32, device;  k_keep [B] int32, device, out;  tau_cov in [0, 1]
  *   ws: at least tsa_workspace_bytes() bytes (uses a part of it) */
 int tsa_coverage_budget(const tsa_desc* desc, const float* scores, double tau_cov, int32_t* k_keep,
@@ -260,19 +266,6 @@ int tsa_layer_drift(const void* h_in, const void* h_out, int64_t n_tokens, int32
  *   rank[l] = (1/n) * #{k : R_k <= R_l};  is_sparse[l] = rank[l] <= delta  (the paper uses delta = 0.5).
  *   drift [n_layers] fp32, host;  is_sparse [n_layers] int32, host, out (1 = apply Token Sparse Attention). */
 int tsa_sparse_layers(const float* drift, int32_t n_layers, double delta, int32_t* is_sparse);
-
-/* Roofline calibration (not a step of the method): runs a bare loop of 8 * iters bf16 MFMAs
- * (32x32x16) per wavefront, 4 wavefronts per workgroup, `blocks` workgroups, with operand values taken
- * from `operands`, and records the shader clock it ran at.  The sustained matrix rate of the chip
- * depends on the operand values (clock under power limit); a benchmark uses this to report the
- * rate a pure MFMA stream reaches on the workload's own data beside the published peak.
- *   operands: device, at least 64 KiB of bf16 values;  sink: device, blocks * 256 fp32 (scratch output)
- *   clocks: device int64[2], out: {shader-clock cycles, wall-clock ticks} of workgroup 0's loop
- *   flops (host, out, may be NULL): floating-point operations of the whole launch
- *   wall_clock_khz (host, out, may be NULL): rate of the wall clock in kHz
- * The caller times the launch (events on `stream`) and divides. */
-int tsa_mfma_probe(const void* operands, int32_t iters, int32_t blocks, float* sink, int64_t* clocks,
-                   double* flops, int32_t* wall_clock_khz, void* stream);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,39 @@
+/*
+ * libtsa -- measurement support.  Nothing here is a step of Token Sparse Attention: these entry points
+ * exist for benchmarks that want to state what the chip itself sustains next to a kernel's rate.
+ * Same conventions as tsa.h (device pointers owned by the caller, status codes, tsa_last_error()).
+ */
+#ifndef TSA_BENCH_H
+#define TSA_BENCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Matrix-pipe calibration: runs a bare loop of 8 * iters bf16 MFMAs
+ * (32x32x16) per wavefront, 4 wavefronts per workgroup, `blocks` workgroups, with operand values taken
+ * from `operands`, and records the shader clock it ran at.  The sustained matrix rate of the chip
+ * depends on the operand values (clock under power limit); a benchmark uses this to report the
+ * rate a pure MFMA stream reaches on the workload's own data beside the published peak.
+ *   operands: device, at least 64 KiB of bf16 values;  sink: device, blocks * 256 fp32 (scratch output)
+ *   clocks: device int64[2], out: {shader-clock cycles, wall-clock ticks} of workgroup 0's loop
+ *   flops (host, out, may be NULL): floating-point operations of the whole launch
+ *   wall_clock_khz (host, out, may be NULL): rate of the wall clock in kHz
+ * The caller times the launch (events on `stream`) and divides. */
+int tsa_mfma_probe(const void* operands, int32_t iters, int32_t blocks, float* sink, int64_t* clocks,
+                   double* flops, int32_t* wall_clock_khz, void* stream);
+
+
+/* Memory-bandwidth calibration: a plain streaming copy dst[i] = src[i] of `bytes` bytes (a multiple of
+ * 16; both pointers 16-byte aligned, device) in 16-byte pieces with non-temporal stores, the access
+ * pattern of the library's gather / scatter kernels without their indirection.  The caller times the
+ * launch; 2 * bytes / time is the rate a mover can reach on this chip. */
+int tsa_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSA_BENCH_H */

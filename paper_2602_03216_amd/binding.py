@@ -15,10 +15,10 @@ from . import build as _build
 TSA_OK, TSA_ERR_ARG, TSA_ERR_UNSUPPORTED, TSA_ERR_WORKSPACE, TSA_ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_bytes", "tsa_score", "tsa_coverage_budget",
-           "tsa_score_queries", "tsa_gather_queries", "tsa_pool_queries_workspace_bytes", "tsa_pool_queries",
+           "tsa_score_queries_workspace_bytes", "tsa_score_queries", "tsa_gather_queries", "tsa_pool_queries_workspace_bytes", "tsa_pool_queries",
            "tsa_select", "tsa_compress", "tsa_attend_workspace_bytes", "tsa_attend", "tsa_decompress", "tsa_compress_v_tiles", "tsa_attend_fused", "tsa_forward",
            "tsa_forward_dynamic_workspace_bytes", "tsa_forward_dynamic",
-           "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe")
+           "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe", "tsa_copy_probe")
 
 
 class TsaError(RuntimeError):
@@ -77,6 +77,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     ip = ctypes.POINTER(i32)
     lib.tsa_score_queries.restype = ctypes.c_int
     lib.tsa_score_queries.argtypes = [dp, vp, ip, i32, vp, vp, vp, sz, vp]
+    lib.tsa_score_queries_workspace_bytes.restype = sz
+    lib.tsa_score_queries_workspace_bytes.argtypes = [dp, i32]
+    lib.tsa_copy_probe.restype = ctypes.c_int
+    lib.tsa_copy_probe.argtypes = [vp, vp, sz, vp]
     lib.tsa_gather_queries.restype = ctypes.c_int
     lib.tsa_gather_queries.argtypes = [dp, vp, ip, i32, vp, vp]
     lib.tsa_pool_queries_workspace_bytes.restype = sz
@@ -167,8 +171,14 @@ def _host_ints(values):
     return (ctypes.c_int32 * len(values))(*[int(v) for v in values])
 
 
-def tsa_score_queries(desc, Qsel, qpos, K, scores, ws):
+def tsa_score_queries_workspace_bytes(desc, n) -> int:
+    return int(load_library().tsa_score_queries_workspace_bytes(ctypes.byref(desc), n))
+
+
+def tsa_score_queries(desc, Qsel, qpos, K, scores, ws=None):
     """qpos: sequence of host ints (ascending positions of the rows of Qsel)."""
+    if ws is None:
+        ws = torch.empty(max(256, tsa_score_queries_workspace_bytes(desc, len(qpos))), dtype=torch.uint8, device=K.device)
     p, n = _ws(ws)
     _check(load_library().tsa_score_queries(ctypes.byref(desc), _ptr(Qsel), _host_ints(qpos), len(qpos), _ptr(K),
                                             _ptr(scores), p, n, _stream()))
@@ -280,6 +290,14 @@ def tsa_mfma_probe(operands, iters, blocks, sink, clocks):
     _check(load_library().tsa_mfma_probe(_ptr(operands), iters, blocks, _ptr(sink), _ptr(clocks),
                                          ctypes.byref(flops), ctypes.byref(khz), _stream()))
     return flops.value, khz.value
+
+
+def tsa_copy_probe(src, dst):
+    """Queues the streaming copy dst = src (same byte size, a multiple of 16)."""
+    nbytes = src.numel() * src.element_size()
+    if nbytes != dst.numel() * dst.element_size():
+        raise TsaError(TSA_ERR_ARG, "src and dst differ in size")
+    _check(load_library().tsa_copy_probe(_ptr(src), _ptr(dst), nbytes, _stream()))
 
 
 def alloc_attend_workspace(desc, Lc, kv_heads, device="cuda"):

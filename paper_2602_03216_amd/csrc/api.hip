@@ -1,12 +1,14 @@
 // C-ABI layer of libtsa: argument validation on the host, workspace carving, kernel launches.
 // Nothing here allocates device memory or synchronises with the host.
 #include "../../include/tsa.h"
+#include "../../include/tsa_bench.h"
 #include "tsa_internal.h"
 
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 namespace {
 
@@ -72,6 +74,14 @@ int check_k(const tsa::Dims& dm, int32_t k_keep) {
   return TSA_OK;
 }
 
+// The always-kept tokens must fit into the set (selection only: the other steps ignore them).
+int check_forced(const tsa::Dims& dm, int32_t k_keep) {
+  if (dm.force_first + dm.force_last > k_keep)
+    return fail(TSA_ERR_ARG, "force_first + force_last (%d) exceeds k_keep (%d): the forced tokens would not all be kept",
+                dm.force_first + dm.force_last, k_keep);
+  return TSA_OK;
+}
+
 int check_ptr(const void* p, const char* name, bool optional = false) {
   if (!p) return optional ? TSA_OK : fail(TSA_ERR_ARG, "%s is NULL", name);
   if (misaligned(p)) return fail(TSA_ERR_ARG, "%s is not 16-byte aligned", name);
@@ -129,7 +139,7 @@ ForwardWs forward_layout(const tsa::Dims& dm, int32_t k) {
 
 extern "C" {
 
-int tsa_version(void) { return 9; }
+int tsa_version(void) { return 10; }
 
 const char* tsa_last_error(void) { return g_err; }
 
@@ -175,11 +185,20 @@ int tsa_score_queries(const tsa_desc* desc, const void* Qsel, const int32_t* qpo
   tsa::Dims dm;
   int rc;
   if ((rc = check_desc(desc, &dm))) return rc;
-  if (n != dm.last_q) return fail(TSA_ERR_ARG, "n (%d) must equal desc.last_q (%d)", n, dm.last_q);
+  if (n < 1 || n > 128) return fail(TSA_ERR_ARG, "n (%d) must lie in [1, 128]", n);
+  dm.last_q = n;                                         // the query set of this call replaces the recent-query window
   if ((rc = check_positions(qpos, n, dm.L))) return rc;
   if ((rc = check_ptr(Qsel, "Qsel")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(scores, "scores"))) return rc;
   if ((rc = check_ws(ws, ws_bytes, tsa::score_ws_bytes(dm)))) return rc;
   return hip_status(tsa::launch_score_queries(dm, Qsel, qpos, K, scores, ws, (hipStream_t)stream), "tsa_score_queries");
+}
+
+size_t tsa_score_queries_workspace_bytes(const tsa_desc* desc, int32_t n) {
+  tsa::Dims dm;
+  if (check_desc(desc, &dm) != TSA_OK) return 0;
+  if (n < 1 || n > 128) return 0;
+  dm.last_q = n;
+  return tsa::score_ws_bytes(dm);
 }
 
 int tsa_gather_queries(const tsa_desc* desc, const void* Q, const int32_t* qpos, int32_t n, void* Qsel, void* stream) {
@@ -228,7 +247,7 @@ int tsa_select(const tsa_desc* desc, const float* scores, int32_t k_keep,
                int32_t* idx, int32_t* inv, void* ws, size_t ws_bytes, void* stream) {
   tsa::Dims dm;
   int rc;
-  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep))) return rc;
+  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep)) || (rc = check_forced(dm, k_keep))) return rc;
   if ((rc = check_ptr(scores, "scores")) || (rc = check_ptr(idx, "idx")) || (rc = check_ptr(inv, "inv", true))) return rc;
   if ((rc = check_ws(ws, ws_bytes, tsa::select_ws_bytes(dm)))) return rc;
   return hip_status(tsa::launch_select(dm, scores, k_keep, idx, inv, ws, (hipStream_t)stream), "tsa_select");
@@ -324,7 +343,7 @@ int tsa_forward(const tsa_desc* desc, const void* Q, const void* K, const void* 
                 void* ws, size_t ws_bytes, void* stream) {
   tsa::Dims dm;
   int rc;
-  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep))) return rc;
+  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep)) || (rc = check_forced(dm, k_keep))) return rc;
   if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(V, "V"))) return rc;
   if (!O && !residual) return fail(TSA_ERR_ARG, "both O and residual are NULL");
   if ((rc = check_ptr(O, "O", true)) || (rc = check_ptr(residual, "residual", true)) || (rc = check_ptr(idx_out, "idx_out", true)))
@@ -367,7 +386,7 @@ int tsa_forward_dynamic(const tsa_desc* desc, const void* Q, const void* K, cons
                         void* ws, size_t ws_bytes, void* stream) {
   tsa::Dims dm;
   int rc;
-  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_max))) return rc;
+  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_max)) || (rc = check_forced(dm, k_max))) return rc;
   if (!(tau_cov >= 0.0) || !(tau_cov <= 1.0)) return fail(TSA_ERR_ARG, "tau_cov must lie in [0, 1]");
   if ((rc = check_ptr(Q, "Q")) || (rc = check_ptr(K, "K")) || (rc = check_ptr(V, "V"))) return rc;
   if (!O && !residual) return fail(TSA_ERR_ARG, "both O and residual are NULL");
@@ -387,7 +406,8 @@ int tsa_forward_dynamic(const tsa_desc* desc, const void* Q, const void* K, cons
   // Algorithm 1 in its own order: scores, budget from the cross-head mass, selection with that budget;
   // every later launch is sized for k_max and reads the count of its batch entry from k_dev.
   if ((rc = hip_status(tsa::launch_score(dm, Q, K, scores, base + w.score_ws, st), "tsa_forward_dynamic(score)"))) return rc;
-  if ((rc = hip_status(tsa::launch_budget(dm, scores, tau_cov, k_dev, base + w.budget_ws, st, k_max), "tsa_forward_dynamic(budget)"))) return rc;
+  if ((rc = hip_status(tsa::launch_budget(dm, scores, tau_cov, k_dev, base + w.budget_ws, st, k_max, dm.force_first + dm.force_last),
+                       "tsa_forward_dynamic(budget)"))) return rc;
   if ((rc = hip_status(tsa::launch_select(dm, scores, k_max, idx, inv, base + w.select_ws, st, k_dev), "tsa_forward_dynamic(select)"))) return rc;
   if ((rc = hip_status(tsa::launch_compress_tiled(dm, Q, K, V, idx, k_max, nullptr, nullptr, Vt, st, k_dev), "tsa_forward_dynamic(V tiles)"))) return rc;
   if ((rc = hip_status(tsa::launch_attend_fused(dm, Q, K, Vt, idx, inv, k_max, block_list, block_size, max_blocks_per_row,
@@ -444,6 +464,13 @@ int tsa_mfma_probe(const void* operands, int32_t iters, int32_t blocks, float* s
     *wall_clock_khz = khz;
   }
   return hip_status(tsa::launch_mfma_probe(operands, iters, blocks, sink, (long long*)clocks, (hipStream_t)stream), "tsa_mfma_probe");
+}
+
+int tsa_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
+  int rc;
+  if ((rc = check_ptr(src, "src")) || (rc = check_ptr(dst, "dst"))) return rc;
+  if (bytes % 16 != 0) return fail(TSA_ERR_ARG, "bytes must be a multiple of 16");
+  return hip_status(tsa::launch_copy_probe(src, dst, bytes, (hipStream_t)stream), "tsa_copy_probe");
 }
 
 }  // extern "C"

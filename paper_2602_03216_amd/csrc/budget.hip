@@ -1,6 +1,6 @@
-// Dynamic Token Coverage budget: Algorithm 1 of the paper, steps "aggregate and normalize token
-// scores across heads", "sort tokens by ascending importance", "determine the number of sparse
-// token".  s_l[t] = sum_h s_h[t] (normalised by its total); k_sparse = the smallest k whose k
+// Dynamic Token Coverage budget: the budget steps of Algorithm 1 of the paper (Section 2.3): cross-head
+// sum of the token scores, normalisation, ascending order, cumulative-mass threshold.
+// s_l[t] = sum_h s_h[t] (normalised by its total); k_sparse = the smallest k whose k
 // least important tokens carry a cumulative mass >= tau; k_keep = L - k_sparse.
 //
 // No sort is needed: the answer only depends on the value at which the ascending cumulative mass
@@ -9,8 +9,12 @@
 // the prefix found so far, a 256-bin histogram of (count, mass); the next kernel walks the bins
 // upwards until count/mass below plus the bin's mass reaches the target.  After the last pass
 // the bin is a single fp32 value v, and the number of tied tokens to take is
-// ceil((target - mass_below) / v).  Masses are accumulated in fp64 (atomics on integers and
-// doubles: the result does not depend on the order beyond 1e-16 relative).
+// ceil((target - mass_below) / v).
+// Masses are EXACT and do not depend on the order of the additions: the keys of one bin differ by at
+// most one step of the binary exponent (first pass) or share it (later passes), so a bin's mass is kept
+// as the integer sum of the 24-bit significands (shifted by the lowest exponent bit), accumulated with
+// integer atomics, and becomes a double only when the bins are walked, in a fixed order.  Two runs on
+// the same scores give the same count bit for bit.
 #include "tsa_internal.h"
 
 namespace tsa {
@@ -28,8 +32,8 @@ struct BudState {
 };
 
 struct BudRow {
-  double total;
-  double mass[4][256];
+  double total;                        // written by the first slice of pass 1, read by the later launches
+  unsigned long long isum[4][256];     // per bin: sum of significands, in units of 2^(E - 150), E = bin_exponent()
   uint32_t count[4][256];
   BudState state[5];     // state[p]: before pass p; state[4]: final
 };
@@ -42,6 +46,7 @@ struct BudArgs {
   int Hq, L;
   double tau;
   int k_max;             // upper bound of the result (capacity of the caller's buffers)
+  int k_min;             // lower bound of the result (at least 1)
 };
 
 __device__ __forceinline__ uint32_t order_key(float f) {
@@ -53,39 +58,53 @@ __device__ __forceinline__ float key_value(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
 
-__global__ void zero_rows_kernel(BudRow* rows, int n_words) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n_words) ((uint32_t*)rows)[i] = 0u;
+// A float as significand x 2^(exponent - 150): finite v, sig < 2^24 (subnormals: exponent field 1).
+__device__ __forceinline__ void split_float(float v, uint32_t& sig, int& e) {
+  const uint32_t u = __float_as_uint(v);
+  e = (int)((u >> 23) & 255u);
+  sig = u & 0x7fffffu;
+  if (e) sig |= 0x800000u; else e = 1;
+}
+// Exponent unit of a bin's integer sum: the exponent field of the bin's smallest magnitude.  The first
+// pass fixes sign and the upper seven exponent bits (the low bit is free: significands of the larger
+// exponent are shifted left by one); later passes fix the whole exponent.  `key_prefix`: any key of the bin.
+__device__ __forceinline__ int bin_exponent(uint32_t key_prefix, int pass) {
+  const uint32_t u = (key_prefix & 0x80000000u) ? (key_prefix & 0x7fffffffu) : ~key_prefix;   // back to float bits
+  int e = (int)((u >> 23) & 255u);
+  if (pass == 0) e &= ~1;
+  return e < 1 ? 1 : e;
+}
+__device__ __forceinline__ double bin_mass(unsigned long long isum, uint32_t key_prefix, int pass) {
+  const double m = ldexp((double)isum, bin_exponent(key_prefix, pass) - 150);     // isum < 2^53: exact
+  return (key_prefix & 0x80000000u) ? m : -m;                                     // keys below 2^31 are negative scores
 }
 
-// s_l = sum over heads, fp32, in head order; total in fp64
+// s_l = sum over heads, fp32, in head order; also clears the histograms of the four passes
 __global__ __launch_bounds__(kThreads) void head_sum_kernel(BudArgs a) {
-  __shared__ double wsum[kWaves];
   const long long b = blockIdx.y;
   const int t = blockIdx.x * kThreads + threadIdx.x;
-  float acc = 0.f;
   if (t < a.L) {
+    float acc = 0.f;
     for (int h = 0; h < a.Hq; ++h) acc += a.scores[(b * a.Hq + h) * a.L + t];
     a.sl[b * a.L + t] = acc;
   }
-  double v = (double)acc;
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = v;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double s = 0.0;
-    for (int w = 0; w < kWaves; ++w) s += wsum[w];
-    atomicAdd(&a.rows[b].total, s);
-  }
+  constexpr int n_words = (int)(sizeof(BudRow) / 4);
+  uint32_t* row = (uint32_t*)(a.rows + b);
+  for (int i = t; i < n_words; i += gridDim.x * kThreads) row[i] = 0u;
 }
 
 // Walks the 256 bins of one pass upwards (first wavefront): lane l owns bins 4l..4l+3.
-__device__ __forceinline__ BudState next_state(const BudRow* rw, int pass, BudState st, double target, int shift, int lane) {
+// `total` (may be NULL): receives the mass of all bins of the pass (every lane gets the same value).
+__device__ __forceinline__ BudState next_state(const BudRow* rw, int pass, BudState st, double tau, double* total, int shift,
+                                               int lane) {
   double ms[4];
   uint32_t cn[4];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) { ms[j] = rw->mass[pass][4 * lane + j]; cn[j] = rw->count[pass][4 * lane + j]; }
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t key_prefix = st.prefix | ((uint32_t)(4 * lane + j) << shift);
+    ms[j] = bin_mass(rw->isum[pass][4 * lane + j], key_prefix, pass);
+    cn[j] = rw->count[pass][4 * lane + j];
+  }
   const double mine = ms[0] + ms[1] + ms[2] + ms[3];
   const uint32_t minec = cn[0] + cn[1] + cn[2] + cn[3];
   double incl = mine;
@@ -95,6 +114,13 @@ __device__ __forceinline__ BudState next_state(const BudRow* rw, int pass, BudSt
     const double up = __shfl_up(incl, d);
     const uint32_t upc = __shfl_up(inclc, d);
     if (lane >= d) { incl += up; inclc += upc; }
+  }
+  double target;
+  if (total) {                          // first pass: its bins hold every token, their mass is the total
+    *total = __shfl(incl, 63);
+    target = tau * *total;
+  } else {
+    target = tau * rw->total;
   }
   // first lane whose bins reach the target; if none does (tau >= 1 up to rounding), the last lane
   // that holds any token
@@ -127,7 +153,7 @@ __device__ __forceinline__ BudState next_state(const BudRow* rw, int pass, BudSt
 
 template <int PASS>
 __global__ __launch_bounds__(kThreads) void bud_hist_kernel(BudArgs a) {
-  __shared__ double hmass[256];
+  __shared__ unsigned long long hsum[256];
   __shared__ uint32_t hcount[256];
   __shared__ BudState sh_state;
   const int slice = blockIdx.x;
@@ -139,13 +165,17 @@ __global__ __launch_bounds__(kThreads) void bud_hist_kernel(BudArgs a) {
   if (wave == 0) {
     BudState st;
     if (PASS == 0) { st.prefix = 0u; st.count_below = 0u; st.mass_below = 0.0; }
-    else st = next_state(rw, PASS - 1, rw->state[PASS - 1], a.tau * rw->total, shift + 8, lane);
+    else {
+      double total;
+      st = next_state(rw, PASS - 1, rw->state[PASS - 1], a.tau, PASS == 1 ? &total : nullptr, shift + 8, lane);
+      if (PASS == 1 && lane == 0 && slice == 0) rw->total = total;
+    }
     if (lane == 0) {
       sh_state = st;
       if (slice == 0) rw->state[PASS] = st;
     }
   }
-  if (tid < 256) { hmass[tid] = 0.0; hcount[tid] = 0u; }
+  if (tid < 256) { hsum[tid] = 0ull; hcount[tid] = 0u; }
   __syncthreads();
   const uint32_t prefix = sh_state.prefix;
   constexpr uint32_t himask = PASS == 0 ? 0u : (0xffffffffu << (shift + 8));
@@ -155,14 +185,17 @@ __global__ __launch_bounds__(kThreads) void bud_hist_kernel(BudArgs a) {
     const uint32_t key = order_key(v);
     if ((key & himask) == prefix) {
       const uint32_t dg = (key >> shift) & 255u;
+      uint32_t sig;
+      int e;
+      split_float(v, sig, e);
       atomicAdd(&hcount[dg], 1u);
-      atomicAdd(&hmass[dg], (double)v);
+      atomicAdd(&hsum[dg], (unsigned long long)sig << (e - bin_exponent(key, PASS)));   // shift is 0 or 1
     }
   }
   __syncthreads();
   if (tid < 256 && hcount[tid]) {
     atomicAdd(&rw->count[PASS][tid], hcount[tid]);
-    atomicAdd(&rw->mass[PASS][tid], hmass[tid]);
+    atomicAdd(&rw->isum[PASS][tid], hsum[tid]);
   }
 }
 
@@ -171,7 +204,7 @@ __global__ void bud_final_kernel(BudArgs a) {
   BudRow* rw = a.rows + b;
   const int lane = threadIdx.x;
   const double target = a.tau * rw->total;
-  const BudState st = next_state(rw, 3, rw->state[3], target, 0, lane);
+  const BudState st = next_state(rw, 3, rw->state[3], a.tau, nullptr, 0, lane);
   if (lane == 0) {
     rw->state[4] = st;
     long long k_sparse = 0;
@@ -190,7 +223,7 @@ __global__ void bud_final_kernel(BudArgs a) {
       k_sparse = (long long)st.count_below + j;
     }
     long long keep = (long long)a.L - k_sparse;
-    if (keep < 1) keep = 1;
+    if (keep < a.k_min) keep = a.k_min;
     if (keep > a.k_max) keep = a.k_max;
     a.k_keep[b] = (int32_t)keep;
   }
@@ -205,16 +238,15 @@ size_t budget_ws_bytes(const Dims& dm) {
 }
 
 hipError_t launch_budget(const Dims& dm, const float* scores, double tau_cov, int32_t* k_keep, void* ws, hipStream_t st,
-                         int k_max) {
+                         int k_max, int k_min) {
   BudArgs a;
   a.k_max = k_max > 0 ? k_max : dm.L;
+  a.k_min = k_min > 1 ? k_min : 1;
   a.scores = scores;
   a.rows = (BudRow*)ws;
   a.sl = (float*)((char*)ws + align256((size_t)dm.B * sizeof(BudRow)));
   a.k_keep = k_keep;
   a.Hq = dm.Hq; a.L = dm.L; a.tau = tau_cov;
-  const int n_words = (int)((size_t)dm.B * sizeof(BudRow) / 4);
-  zero_rows_kernel<<<(n_words + 255) / 256, 256, 0, st>>>(a.rows, n_words);
   head_sum_kernel<<<dim3((dm.L + kThreads - 1) / kThreads, dm.B), kThreads, 0, st>>>(a);
   const dim3 grid((dm.L + kSlice - 1) / kSlice, dm.B);
   bud_hist_kernel<0><<<grid, kThreads, 0, st>>>(a);

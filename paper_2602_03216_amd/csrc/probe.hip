@@ -32,7 +32,23 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const u32x4* __restrict
   }
 }
 
+// Streaming copy in 16-byte pieces, grid-stride, non-temporal stores: what a pure mover reaches.
+__global__ __launch_bounds__(256) void copy_probe_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, long long n) {
+  const long long stride = (long long)gridDim.x * 256;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += stride)
+    __builtin_nontemporal_store(src[i], dst + i);
+}
+
 }  // namespace
+
+hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st) {
+  const long long n = (long long)(bytes / 16);
+  if (n == 0) return hipSuccess;
+  long long blocks = (n + 256 * 4 - 1) / (256 * 4);      // about four pieces per thread
+  if (blocks > 65536) blocks = 65536;
+  copy_probe_kernel<<<(unsigned)blocks, 256, 0, st>>>((const u32x4*)src, (u32x4*)dst, n);
+  return hipGetLastError();
+}
 
 hipError_t launch_mfma_probe(const void* operands, int iters, int blocks, float* sink, long long* clocks, hipStream_t st) {
   mfma_probe_kernel<<<blocks, 256, 0, st>>>((const u32x4*)operands, sink, clocks, iters);

@@ -15,10 +15,13 @@
 // to go below a few tokens per thread.
 #include "tsa_internal.h"
 
+#include <mutex>
+
 namespace tsa {
 
 namespace {
 
+constexpr int kMaxDevices = 64;
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
 constexpr int kMinSlice = 2048, kMaxSlice = 16384;   // tokens per workgroup (SelArgs::slice)
@@ -381,11 +384,20 @@ hipError_t launch_select(const Dims& dm, const float* scores, int k_keep, int32_
   a.slice = slice_for(dm);
   if (dm.L <= kSmallL) {
     const size_t lds = ((size_t)dm.L + kWaves * 256) * sizeof(uint32_t);
-    static bool attr_set = false;
-    if (!attr_set) {
-      const hipError_t e = hipFuncSetAttribute((const void*)select_small_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+    // the attribute belongs to the kernel as loaded on ONE device: set it once per device, under a lock
+    {
+      static std::mutex mu;
+      static bool attr_set[kMaxDevices] = {};
+      int dev = 0;
+      hipError_t e = hipGetDevice(&dev);
       if (e != hipSuccess) return e;
-      attr_set = true;
+      if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+      std::lock_guard<std::mutex> lock(mu);
+      if (!attr_set[dev]) {
+        e = hipFuncSetAttribute((const void*)select_small_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 4096);
+        if (e != hipSuccess) return e;
+        attr_set[dev] = true;
+      }
     }
     select_small_kernel<<<rows, kThreads, lds, st>>>(a);
     return hipGetLastError();

@@ -65,9 +65,10 @@ hipError_t launch_select(const Dims& dm, const float* scores, int k_keep, int32_
 
 // budget.hip
 size_t budget_ws_bytes(const Dims& dm);
-// k_max > 0: the result is clamped to it (the capacity of the buffers that will hold the selection)
+// k_max > 0: the result is clamped to it (the capacity of the buffers that will hold the selection);
+// k_min: the result is at least max(1, k_min) (the always-kept tokens of the selection that follows)
 hipError_t launch_budget(const Dims& dm, const float* scores, double tau_cov, int32_t* k_keep, void* ws, hipStream_t st,
-                         int k_max = 0);
+                         int k_max = 0, int k_min = 0);
 
 // drift.hip
 size_t drift_ws_bytes(long long n_tokens);
@@ -112,5 +113,7 @@ hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, con
 
 // probe.hip: bare MFMA loop, 8 * iters MFMAs per wavefront, 4 wavefronts per workgroup
 hipError_t launch_mfma_probe(const void* operands, int iters, int blocks, float* sink, long long* clocks, hipStream_t st);
+// probe.hip: streaming copy of `bytes` bytes (a multiple of 16)
+hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 
 }  // namespace tsa

@@ -18,9 +18,11 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    header = open(os.path.join(ROOT, "include", "tsa.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(tsa_[a-z_]+)\s*\(", header))
+    declared = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):       # tsa.h (the method) and tsa_bench.h (measurement support)
+        header = open(os.path.join(ROOT, "include", name)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        declared |= set(re.findall(r"\b(tsa_[a-z_]+)\s*\(", header))
     assert declared == set(tsa.EXPORTS)
     for name in declared:
         assert getattr(lib, name) is not None
@@ -28,7 +30,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_desc_struct_matches_header(lib):
     assert ctypes.sizeof(tsa.tsa_desc) == 120
-    assert lib.tsa_version() == 9
+    assert lib.tsa_version() == 10
 
 
 def test_keep_count_matches_oracle_rule(lib):
@@ -67,6 +69,15 @@ def test_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert lib.tsa_score(dp, fake, fake, fake, fake, 16, None) == tsa.TSA_ERR_WORKSPACE
     assert lib.tsa_select(dp, fake, 0, fake, fake, None, 0, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_select(dp, fake, 1025, fake, fake, None, 0, None) == tsa.TSA_ERR_ARG
+    forced = tsa.make_desc(1, 4, 4, 1024, 64, force_first=4, force_last=7)       # 11 always-kept tokens need k_keep >= 11
+    assert lib.tsa_select(ctypes.byref(forced), fake, 10, fake, fake, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
+    assert "force_first" in tsa.tsa_last_error()
+    assert lib.tsa_forward(ctypes.byref(forced), fake, fake, fake, 10, None, 0, 0, fake, None, None, fake, 1 << 40, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_forward_dynamic(ctypes.byref(forced), fake, fake, fake, 0.01, 10, None, 0, 0, fake, None, None, None, fake, 1 << 40, None) == tsa.TSA_ERR_ARG
+    # the general scorer takes 1..128 query rows whatever desc.last_q says
+    assert lib.tsa_score_queries_workspace_bytes(dp, 0) == 0 and lib.tsa_score_queries_workspace_bytes(dp, 129) == 0
+    assert lib.tsa_score_queries_workspace_bytes(dp, 100) >= lib.tsa_score_queries_workspace_bytes(dp, 3) > 0
+    assert lib.tsa_copy_probe(fake, fake, 24, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_compress(dp, fake, fake, fake, None, 16, fake, fake, fake, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_attend(dp, fake, fake, fake, 0, 4, None, 0, 0, fake, None, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_attend(dp, fake, fake, fake, 16, 3, None, 0, 0, fake, None, fake, 1 << 30, None) == tsa.TSA_ERR_ARG

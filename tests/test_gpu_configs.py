@@ -4,8 +4,11 @@
 What the oracle can compute in full is compared in full: scores, index sets (bit-exact, the
 inputs carry a margin at every k of the sweep), the zero rows of the decompressed output.
 Attention outputs are compared in full where the oracle finishes in seconds (workloads 1-2)
-and on sampled compacted rows per head otherwise (first 8, last 8, 48 seeded random rows: each
-sampled row is an exact O(k d) computation of the oracle)."""
+and on sampled compacted rows per head otherwise: the first 8, the last 8, 48 seeded random rows
+and one seeded row out of every 128 consecutive rows, so that every workgroup of the launch (a
+workgroup owns 256 or 128 consecutive query rows of a head) has a row compared with the oracle;
+each sampled row is an exact O(k d) computation of the oracle.  At the 128K workload the fused
+layer is also compared bit for bit, in full, with the separate entry points."""
 import numpy as np
 import pytest
 import torch
@@ -30,6 +33,8 @@ def _sample_rows(k, seed):
     rows = set(range(min(8, k))) | set(range(max(0, k - 8), k))
     if k > 16:
         rows |= set(r.choice(k, size=min(48, k), replace=False).tolist())
+    for lo in range(0, k, 128):                 # one row of every 128-row stretch: no workgroup goes unchecked
+        rows.add(int(r.integers(lo, min(lo + 128, k))))
     return np.array(sorted(rows), dtype=np.int64)
 
 
@@ -122,6 +127,36 @@ def test_workload3_gqa_32k_group_mode(tsa):
 
 def test_workload4_gqa_128k(tsa):
     _run_config(tsa, 4, full_attend=False)
+
+
+def test_workload4_fused_layer_equals_separate_calls_at_full_size(tsa):
+    """128K tokens, tau = 0.75, the launch configuration of the headline measurement: tsa_forward
+    against tsa_score -> tsa_select -> tsa_compress -> tsa_attend -> tsa_decompress, every index and
+    every output element bit for bit (the separate calls are what the oracle checks row by row above)."""
+    inp = gen.make_inputs(4)
+    cfg = inp.cfg
+    B, Hq, Hkv, L, d, Lq = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["L"], cfg["d"], cfg["last_q"]
+    k = orc.keep_count(L, 0.75)
+    Q, K, V = gu.to_dev(inp.Q), gu.to_dev(inp.K), gu.to_dev(inp.V)
+    desc = tsa.make_desc(B, Hq, Hkv, L, d, Lq)
+    ws = tsa.alloc_workspace(desc, k, gu.DEV)
+    s = torch.empty((B, Hq, L), dtype=torch.float32, device=gu.DEV)
+    idx = torch.empty((B, Hq, k), dtype=torch.int32, device=gu.DEV)
+    inv = torch.empty((B, Hq, L), dtype=torch.int32, device=gu.DEV)
+    Qc = torch.empty((B, Hq, k, d), dtype=torch.bfloat16, device=gu.DEV)
+    Kc, Vc, Oc = torch.empty_like(Qc), torch.empty_like(Qc), torch.empty_like(Qc)
+    O1 = torch.full((B, Hq, L, d), 5.0, dtype=torch.bfloat16, device=gu.DEV)
+    tsa.tsa_score(desc, Q, K, s, ws)
+    tsa.tsa_select(desc, s, k, idx, inv, ws)
+    tsa.tsa_compress(desc, Q, K, V, idx, k, Qc, Kc, Vc)
+    tsa.tsa_attend(desc, Qc, Kc, Vc, k, Hq, Oc, tsa.alloc_attend_workspace(desc, k, Hq, gu.DEV))
+    tsa.tsa_decompress(desc, Oc, idx, inv, k, O=O1)
+    O2 = torch.full_like(O1, 7.0)
+    idx2 = torch.empty_like(idx)
+    tsa.tsa_forward(desc, Q, K, V, k, O2, ws, idx_out=idx2)
+    torch.cuda.synchronize()
+    assert torch.equal(idx2, idx)
+    assert torch.equal(O2, O1)
 
 
 def test_workload5_interleaved_stack(tsa):
