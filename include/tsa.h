@@ -147,6 +147,18 @@ int tsa_coverage_budget(const tsa_desc* desc, const float* scores, double tau_co
 int tsa_select(const tsa_desc* desc, const float* scores, int32_t k_keep,
                int32_t* idx, int32_t* inv, void* ws, size_t ws_bytes, void* stream);
 
+/* tsa_select for callers that cannot allocate device memory or carry a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments and same results as
+ * tsa_select, but the histograms, thresholds and per-slice counts live in a static device array of the
+ * library, tsa_select_static_capacity() bytes (8 MiB) per GPU the library runs on, held until the process
+ * ends.  Allocates nothing.  A problem whose scratch does not fit (group_mode 1 keeps B*Hkv*L fp32 sums
+ * there) is rejected with TSA_ERR_UNSUPPORTED.  All calls on one GPU share the array: calls that
+ * overlap on one GPU (different streams, or different threads) race; the array keeps the last call's
+ * contents and every call clears what it needs at zero itself. */
+size_t tsa_select_static_capacity(void);
+int tsa_select_static(const tsa_desc* desc, const float* scores, int32_t k_keep,
+                      int32_t* idx, int32_t* inv, void* stream);
+
 /* Stage 1, compression: gather the rows S_h of Q, K, V into dense contiguous tensors.
  *   idx [B,Hs,k_keep] int32 (from tsa_select)
  *   Qc  [B,Hq,k_keep,d] out.  group_mode 0: Kc, Vc [B,Hq,k_keep,d] (row idx[b,h,r] of KV head h/g);

@@ -18,7 +18,8 @@ EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_byt
            "tsa_score_queries_workspace_bytes", "tsa_score_queries", "tsa_gather_queries", "tsa_pool_queries_workspace_bytes", "tsa_pool_queries",
            "tsa_select", "tsa_compress", "tsa_attend_workspace_bytes", "tsa_attend", "tsa_decompress", "tsa_compress_v_tiles", "tsa_attend_fused", "tsa_forward",
            "tsa_forward_dynamic_workspace_bytes", "tsa_forward_dynamic",
-           "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe", "tsa_copy_probe")
+           "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe", "tsa_copy_probe",
+           "tsa_select_static", "tsa_select_static_capacity")
 
 
 class TsaError(RuntimeError):
@@ -91,6 +92,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_coverage_budget.argtypes = [dp, vp, ctypes.c_double, vp, vp, sz, vp]
     lib.tsa_select.restype = ctypes.c_int
     lib.tsa_select.argtypes = [dp, vp, i32, vp, vp, vp, sz, vp]
+    lib.tsa_select_static.restype = ctypes.c_int
+    lib.tsa_select_static.argtypes = [dp, vp, i32, vp, vp, vp]
+    lib.tsa_select_static_capacity.restype = sz
+    lib.tsa_select_static_capacity.argtypes = []
     lib.tsa_compress.restype = ctypes.c_int
     lib.tsa_compress.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.tsa_attend.restype = ctypes.c_int
@@ -207,6 +212,10 @@ def tsa_coverage_budget(desc, scores, tau_cov, k_keep, ws):
 def tsa_select(desc, scores, k_keep, idx, inv, ws=None):
     p, n = _ws(ws)
     _check(load_library().tsa_select(ctypes.byref(desc), _ptr(scores), k_keep, _ptr(idx), _ptr(inv), p, n, _stream()))
+
+
+def tsa_select_static(desc, scores, k_keep, idx, inv):
+    _check(load_library().tsa_select_static(ctypes.byref(desc), _ptr(scores), k_keep, _ptr(idx), _ptr(inv), _stream()))
 
 
 def tsa_compress(desc, Q, K, V, idx, k_keep, Qc, Kc, Vc):

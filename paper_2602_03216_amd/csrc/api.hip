@@ -10,6 +10,10 @@
 #include <cstring>
 #include <mutex>
 
+#ifndef TSA_STATIC_SCRATCH_BYTES
+#define TSA_STATIC_SCRATCH_BYTES (8u << 20)
+#endif
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -251,6 +255,60 @@ int tsa_select(const tsa_desc* desc, const float* scores, int32_t k_keep,
   if ((rc = check_ptr(scores, "scores")) || (rc = check_ptr(idx, "idx")) || (rc = check_ptr(inv, "inv", true))) return rc;
   if ((rc = check_ws(ws, ws_bytes, tsa::select_ws_bytes(dm)))) return rc;
   return hip_status(tsa::launch_select(dm, scores, k_keep, idx, inv, ws, (hipStream_t)stream), "tsa_select");
+}
+
+}  // extern "C"
+
+// ---- tsa_select_static: selection whose scratch is a static device array of the library ----
+namespace {
+
+constexpr size_t kStaticScratchBytes = TSA_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+
+// Histograms, thresholds and per-slice counts of the selection kernels (what tsa_select takes through
+// `ws`).  One copy per GPU the library runs on, resident until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress: kernels and copies get the address looked up below.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on the current device, looked up once per device.
+int static_scratch(void** out) {
+  int dev = 0, rc;
+  if ((rc = hip_status(hipGetDevice(&dev), "hipGetDevice"))) return rc;
+  if (dev < 0 || dev >= kMaxDevices) return fail(TSA_ERR_UNSUPPORTED, "device ordinal %d: at most %d devices", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if ((rc = hip_status(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)"))) return rc;
+    if (!p) return fail(TSA_ERR_HIP, "hipGetSymbolAddress(scratch) returned NULL");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return TSA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tsa_select_static_capacity(void) { return kStaticScratchBytes; }
+
+int tsa_select_static(const tsa_desc* desc, const float* scores, int32_t k_keep,
+                      int32_t* idx, int32_t* inv, void* stream) {
+  tsa::Dims dm;
+  int rc;
+  if ((rc = check_desc(desc, &dm)) || (rc = check_k(dm, k_keep)) || (rc = check_forced(dm, k_keep))) return rc;
+  if ((rc = check_ptr(scores, "scores")) || (rc = check_ptr(idx, "idx")) || (rc = check_ptr(inv, "inv", true))) return rc;
+  const size_t need = tsa::select_ws_bytes(dm);
+  if (need > kStaticScratchBytes)
+    return fail(TSA_ERR_UNSUPPORTED, "tsa_select_static: this problem needs %zu bytes of scratch, the static buffer holds %zu "
+                "(use tsa_select with a workspace)", need, kStaticScratchBytes);
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws))) return rc;
+  // the kernels clear the part of the scratch that has to start at zero themselves
+  return hip_status(tsa::launch_select(dm, scores, k_keep, idx, inv, ws, (hipStream_t)stream), "tsa_select_static");
 }
 
 int tsa_compress(const tsa_desc* desc, const void* Q, const void* K, const void* V,
