@@ -33,6 +33,12 @@ int tsa_mfma_probe(const void* operands, int32_t iters, int32_t blocks, float* s
  * launch; 2 * bytes / time is the rate a mover can reach on this chip. */
 int tsa_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
 
+/* Form of the attention kernel for the launches that follow, process-wide: 0 = chosen per launch from
+ * the problem size (the default), 1 = 256 query rows per workgroup, 2 = 128 query rows per workgroup with
+ * the keys of every tile split over two groups of wavefronts.  Both forms compute the same attention
+ * (results agree within rounding, not bit for bit); a benchmark uses this to time one against the other. */
+int tsa_bench_set_attend_form(int32_t form);
+
 #ifdef __cplusplus
 }
 #endif

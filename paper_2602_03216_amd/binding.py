@@ -18,7 +18,7 @@ EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_byt
            "tsa_score_queries_workspace_bytes", "tsa_score_queries", "tsa_gather_queries", "tsa_pool_queries_workspace_bytes", "tsa_pool_queries",
            "tsa_select", "tsa_compress", "tsa_attend_workspace_bytes", "tsa_attend", "tsa_decompress", "tsa_compress_v_tiles", "tsa_attend_fused", "tsa_forward",
            "tsa_forward_dynamic_workspace_bytes", "tsa_forward_dynamic",
-           "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe", "tsa_copy_probe",
+           "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe", "tsa_copy_probe", "tsa_bench_set_attend_form",
            "tsa_select_static", "tsa_select_static_capacity")
 
 
@@ -80,6 +80,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_score_queries.argtypes = [dp, vp, ip, i32, vp, vp, vp, sz, vp]
     lib.tsa_score_queries_workspace_bytes.restype = sz
     lib.tsa_score_queries_workspace_bytes.argtypes = [dp, i32]
+    lib.tsa_bench_set_attend_form.restype = ctypes.c_int
+    lib.tsa_bench_set_attend_form.argtypes = [i32]
     lib.tsa_copy_probe.restype = ctypes.c_int
     lib.tsa_copy_probe.argtypes = [vp, vp, sz, vp]
     lib.tsa_gather_queries.restype = ctypes.c_int
@@ -299,6 +301,10 @@ def tsa_mfma_probe(operands, iters, blocks, sink, clocks):
     _check(load_library().tsa_mfma_probe(_ptr(operands), iters, blocks, _ptr(sink), _ptr(clocks),
                                          ctypes.byref(flops), ctypes.byref(khz), _stream()))
     return flops.value, khz.value
+
+
+def tsa_bench_set_attend_form(form: int):
+    _check(load_library().tsa_bench_set_attend_form(form))
 
 
 def tsa_copy_probe(src, dst):

@@ -10,13 +10,14 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libtsa.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "budget.hip", "drift.hip", "gather_scatter.hip", "probe.hip", "attend.hip"]
+SOURCES = ["api.hip", "score.hip", "select.hip", "budget.hip", "drift.hip", "gather_scatter.hip", "probe.hip", "attend.hip", "attend_split.hip"]
 # -packed-fp32-ops is switched off: the compiler must not form packed fp32 instructions.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 # per-file additions (attend: let the register allocator place MFMA results in VGPRs or AGPRs
 # per instruction instead of forcing every accumulator into AGPRs)
-EXTRA = {"attend.hip": os.environ.get("TSA_ATTEND_FLAGS", "-mllvm -amdgpu-mfma-vgpr-form").split()}
+_ATTEND_FLAGS = os.environ.get("TSA_ATTEND_FLAGS", "-mllvm -amdgpu-mfma-vgpr-form").split()
+EXTRA = {"attend.hip": _ATTEND_FLAGS, "attend_split.hip": _ATTEND_FLAGS}
 _NOISE = "packed-fp32-ops"
 
 

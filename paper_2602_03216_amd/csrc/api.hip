@@ -524,6 +524,12 @@ int tsa_mfma_probe(const void* operands, int32_t iters, int32_t blocks, float* s
   return hip_status(tsa::launch_mfma_probe(operands, iters, blocks, sink, (long long*)clocks, (hipStream_t)stream), "tsa_mfma_probe");
 }
 
+int tsa_bench_set_attend_form(int32_t form) {
+  if (form < 0 || form > 2) return fail(TSA_ERR_ARG, "form must be 0, 1 or 2");
+  tsa::set_attend_form(form);
+  return TSA_OK;
+}
+
 int tsa_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
   int rc;
   if ((rc = check_ptr(src, "src")) || (rc = check_ptr(dst, "dst"))) return rc;

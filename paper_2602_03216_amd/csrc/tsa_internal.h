@@ -111,6 +111,10 @@ hipError_t launch_attend_fused(const Dims& dm, const void* Q, const void* K, con
                                int max_blocks_per_row, void* Oc, void* O, void* residual, hipStream_t st,
                                const int32_t* k_dev = nullptr);
 
+// attend.hip: 0 = the form of the attention kernel is chosen per launch (default), 1 = 256 query rows per
+// workgroup always, 2 = 128 rows with split keys always (measurement support)
+void set_attend_form(int form);
+
 // probe.hip: bare MFMA loop, 8 * iters MFMAs per wavefront, 4 wavefronts per workgroup
 hipError_t launch_mfma_probe(const void* operands, int iters, int blocks, float* sink, long long* clocks, hipStream_t st);
 // probe.hip: streaming copy of `bytes` bytes (a multiple of 16)

@@ -19,6 +19,16 @@ def tsa():
     return binding
 
 
+@pytest.fixture(params=[1, 2], ids=["rows256", "rows128_split"])
+def attend_form(request, tsa):
+    """The attention kernel has two forms (256 query rows per workgroup; 128 rows with the keys of a tile
+    split over two groups of wavefronts) and picks one per launch from the problem size.  Tests that
+    take this fixture run once with each form pinned, so both meet the oracle on every shape."""
+    tsa.tsa_bench_set_attend_form(request.param)
+    yield request.param
+    tsa.tsa_bench_set_attend_form(0)
+
+
 def _rng(seed):
     return np.random.Generator(np.random.PCG64(seed))
 
@@ -203,7 +213,7 @@ def test_compress_keep_all_is_identity(tsa):
     (1, 2, 2, 1, 128), (1, 2, 2, 63, 128), (1, 2, 1, 64, 128), (1, 4, 2, 65, 64), (2, 2, 2, 128, 128),
     (1, 3, 3, 129, 128), (1, 8, 2, 300, 128), (1, 4, 4, 256, 64), (1, 9, 3, 1000, 128), (1, 2, 2, 2049, 64),
 ])
-def test_attend_matches_oracle(tsa, B, Hq, Hk, Lc, d):
+def test_attend_matches_oracle(tsa, attend_form, B, Hq, Hk, Lc, d):
     r = _rng(400 + Lc + d)
     Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d))
     desc = tsa.make_desc(B, Hq, Hk, max(Lc, 1), d, 1)
@@ -222,7 +232,7 @@ def test_attend_matches_oracle(tsa, B, Hq, Hk, Lc, d):
         assert np.array_equal(gu.from_dev(O)[0, h, 0], Vb[0, h // g, 0])
 
 
-def test_attend_large_logits_and_scale(tsa):
+def test_attend_large_logits_and_scale(tsa, attend_form):
     r = _rng(21)
     B, H, Lc, d = 1, 2, 500, 128
     Qb, Kb, Vb = gu.rand_bits(r, (B, H, Lc, d), 4.0), gu.rand_bits(r, (B, H, Lc, d), 4.0), gu.rand_bits(r, (B, H, Lc, d))
@@ -233,7 +243,7 @@ def test_attend_large_logits_and_scale(tsa):
     gu.assert_output_close(gu.from_dev(O), orc.f64_to_bf16(want), "attend(large logits)")
 
 
-def test_attend_logits_growing_along_the_keys(tsa):
+def test_attend_logits_growing_along_the_keys(tsa, attend_form):
     """Keys grow along the sequence (logit of key c about 0.066 c nats, 190 log2 units over the row):
     the running max is raised every tile or two, in the middle of the pipelined iterations, where the
     half tile that waits for its exponentials has to be shifted together with the accumulator."""
@@ -256,7 +266,7 @@ def test_attend_logits_growing_along_the_keys(tsa):
 # block (visited by half of the workgroup only) and the diagonal
 @pytest.mark.parametrize("Lc,window,Bs", [(1000, 256, 128), (1300, 128, 128), (640, 4096, 128), (3000, 1024, 128),
                                           (1000, 256, 64), (2100, 512, 64), (1500, 512, 256), (3000, 1024, 256)])
-def test_attend_block_list(tsa, Lc, window, Bs):
+def test_attend_block_list(tsa, attend_form, Lc, window, Bs):
     r = _rng(500 + Lc + Bs)
     B, Hq, Hk, d = 1, 4, 2, 128
     Qb, Kb, Vb = gu.rand_bits(r, (B, Hq, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d)), gu.rand_bits(r, (B, Hk, Lc, d))
@@ -278,7 +288,7 @@ def test_attend_block_list(tsa, Lc, window, Bs):
     (2, 2, 257, 128, 64, 257, 0, "direction"),     # keep everything: dense causal attention
     (2, 1, 200, 64, 8, 1, 0, "norm"),              # keep a single token
 ])
-def test_forward_small(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant):
+def test_forward_small(tsa, attend_form, Hq, Hkv, L, d, Lq, k, group_mode, plant):
     from paper_2602_03216_amd import inputs as gen
     from tests.margin import enforce_margin
     cfg = dict(id=90, name="small", B=1, Hq=Hq, Hkv=Hkv, L=L, d=d, last_q=Lq, plant=plant, n_plant=20, norm_factor=3.0,
@@ -298,7 +308,7 @@ def test_forward_small(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant):
     assert not gu.from_dev(O)[np.repeat(~sel, Hq // Hs, axis=1)].any()
 
 
-def test_attend_random_sweep(tsa):
+def test_attend_random_sweep(tsa, attend_form):
     """Seeded sweep: 40 random attention problems (1 to 2600 rows, both head sizes, grouped heads, one or
     two batch entries) with no block list, a sink + window list or per-head vertical + slash lists, at
     the three block sizes: outputs within the bars of the oracle."""
@@ -426,7 +436,7 @@ def test_forward_random_shapes(tsa, Hq, Hkv, L, d, Lq, k, group_mode, plant, poo
     (3, 2, 1, 777, 64, 200, 0, True),
     (2, 4, 2, 520, 128, 1, 0, False),
 ])
-def test_fused_path_equals_the_separate_calls(tsa, B, Hq, Hkv, L, d, k, group_mode, with_blocks):
+def test_fused_path_equals_the_separate_calls(tsa, attend_form, B, Hq, Hkv, L, d, k, group_mode, with_blocks):
     """tsa_forward / tsa_compress_v_tiles + tsa_attend_fused against tsa_score -> tsa_select ->
     tsa_compress -> tsa_attend -> tsa_decompress on the same inputs: gather and scatter are copies
     and the arithmetic is the same, so every output must match bit for bit (the separate calls are
@@ -476,7 +486,7 @@ def test_fused_path_equals_the_separate_calls(tsa, B, Hq, Hkv, L, d, k, group_mo
 
 @pytest.mark.parametrize("Hq,Hk,Lc,d,Bs", [(4, 2, 1000, 128, 128), (3, 3, 1500, 64, 128), (2, 1, 2600, 128, 128),
                                            (4, 2, 1100, 128, 64), (2, 2, 1900, 64, 256)])
-def test_attend_per_head_block_lists(tsa, Hq, Hk, Lc, d, Bs):
+def test_attend_per_head_block_lists(tsa, attend_form, Hq, Hk, Lc, d, Bs):
     """Block-sparse composition with a different pattern for every head (vertical + slash), in blocks
     of 64, 128 and 256 tokens."""
     from paper_2602_03216_amd import inputs as gen
@@ -493,7 +503,7 @@ def test_attend_per_head_block_lists(tsa, Hq, Hk, Lc, d, Bs):
 
 
 @pytest.mark.parametrize("Bs", [128, 64, 256])
-def test_forward_with_per_head_block_lists(tsa, Bs):
+def test_forward_with_per_head_block_lists(tsa, attend_form, Bs):
     """Token selection first, then a per-head block-sparse pattern in compacted space: the whole layer
     against the oracle's."""
     from paper_2602_03216_amd import inputs as gen
@@ -515,7 +525,7 @@ def test_forward_with_per_head_block_lists(tsa, Bs):
     gu.assert_output_close(gu.from_dev(O), ref["O"], "forward(per-head block lists)")
 
 
-def test_random_small_shapes_sweep(tsa):
+def test_random_small_shapes_sweep(tsa, attend_form):
     """Thirty seeded random small problems (odd lengths around the 64-key and 256-row tile edges,
     odd head counts, both head dimensions, batch > 1): attention against the oracle, and the whole
     layer against the separate calls (bit for bit) on index sets the library selected itself."""
