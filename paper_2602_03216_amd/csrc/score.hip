@@ -1,5 +1,5 @@
-// Token scoring: Algorithm 1 of the paper, "attention scores using recent queries" and
-// "token-level scores per head":  A = softmax(Q[-last_q:] K^T * scale) (causal inside the
+// Token scoring: Algorithm 1 of the paper, its first two steps (proxy attention of the most recent
+// queries, then the per-head column sums):  A = softmax(Q[-last_q:] K^T * scale) (causal inside the
 // window), s[h,t] = sum_i A[i,t].
 //
 // Exact two-pass softmax, both passes on bf16 MFMA with fp32 accumulation:
@@ -365,8 +365,11 @@ __global__ __launch_bounds__(kThreads, NQT <= 2 ? 2 : 1) void score_pass2(ScoreA
   constexpr int QP = 32 * NQT;
   constexpr int KS = D + 8;
   __shared__ __attribute__((aligned(16))) __bf16 Ks[2][kTK * KS];
-  const int chunk = blockIdx.x;
-  const long long bkv = blockIdx.y;
+  // Pass 2 walks the (KV head, chunk) pairs in the reverse of pass 1's order: the workgroups that start
+  // first read the keys pass 1 read last, which the memory-side cache still holds when K as a whole
+  // (268 MB at 128K tokens x 8 KV heads) does not fit it.
+  const int chunk = (int)(gridDim.x - 1 - blockIdx.x);
+  const long long bkv = gridDim.y - 1 - blockIdx.y;
   const int kv = (int)(bkv % a.Hkv);
   const long long b = bkv / a.Hkv;
   const int g = a.Hq / a.Hkv;
