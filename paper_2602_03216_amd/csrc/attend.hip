@@ -104,9 +104,8 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const float c_ = c;
   const float inv_c = 1.0f / c;                                    // (the chunk loop of the pipelined iteration has its own c)
 
-  // ---- fused form: zero rows of the full-length output.  The workgroup owns the tokens from its
-  // first selected token up to the next workgroup's first one (the first workgroup of a head starts
-  // at token 0, the last one ends at L) and clears those that inv marks unselected.  The work is
+  // ---- fused form: zero rows of the full-length output.  The workgroup owns a range of the head's
+  // tokens (see below) and clears those that inv marks unselected.  The work is
   // spread over the tile loop, one pass of kThreads / (d/8) rows every z_every iterations (the
   // look-up in inv for the next pass is in flight meanwhile), so the stores drain under the compute
   // instead of holding up the start of the workgroup; what is left when the tiles run out is flushed
@@ -120,8 +119,12 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   int z_every = 1, z_count = 1, z_passes = 1;
   if (zfill) {
     inv_row = a.inv + bkv * a.L;
-    const int tok_lo = qt == 0 ? 0 : idx_row[q0];
-    z_hi = q0 + BM >= Lc ? a.L : idx_row[q0 + BM];
+    // Token range of this workgroup.  Any partition of [0, L) over the query tiles of a head works (a row is
+    // cleared iff inv marks it unselected, whoever looks).  The shares grow linearly with the query tile,
+    // as the number of tile iterations does, so that every workgroup can clear its share inside its loop.
+    const long long nq = nq_tiles, wt = nq * (nq + 1) / 2;
+    const int tok_lo = (int)((long long)a.L * ((long long)qt * (qt + 1) / 2) / wt);
+    z_hi = (int)((long long)a.L * ((long long)(qt + 1) * (qt + 2) / 2) / wt);
     zrow = (u32x4*)(a.Of + a.os.head(b, h)) + (tid % LPR);
     zt = tok_lo + tid / LPR;
     zr = zt < z_hi ? inv_row[zt] : 0;
@@ -490,17 +493,28 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     rotate();
   }
 
-  // ---- fused form: the zero rows the tile loop did not get to, eight look-ups in flight per thread
+  // ---- fused form: the zero rows the tile loop did not get to
   if (zfill) {
-    constexpr int kBatch = 8;
+    // Latency-bound: a batch of look-ups is a memory round trip.  Sixteen rows per thread and batch, the
+    // look-ups of the next batch requested before the stores of the current one (so that waiting for them
+    // never includes waiting for those stores to be acknowledged).
+    constexpr int kBatch = 16;
     if (zr < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)zt * o_pitch16);
-    for (int t0 = zt + RPP; t0 < z_hi; t0 += kBatch * RPP) {
-      int r[kBatch];
+    int t0 = zt + RPP;
+    int r[kBatch];
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j) r[j] = t0 + j * RPP < z_hi ? inv_row[t0 + j * RPP] : 0;
+    for (int j = 0; j < kBatch; ++j) r[j] = t0 + j * RPP < z_hi ? inv_row[t0 + j * RPP] : 0;
+    while (t0 < z_hi) {
+      const int t1 = t0 + kBatch * RPP;
+      int rn[kBatch];
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) rn[j] = t1 + j * RPP < z_hi ? inv_row[t1 + j * RPP] : 0;
 #pragma unroll
       for (int j = 0; j < kBatch; ++j)
         if (r[j] < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)(t0 + j * RPP) * o_pitch16);
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) r[j] = rn[j];
+      t0 = t1;
     }
   }
 

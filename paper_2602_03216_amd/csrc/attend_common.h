@@ -22,6 +22,7 @@ constexpr int BN = kKeyTile;   // keys per tile
 #define TSA_QS 1
 #endif
 
+
 constexpr int kQS = TSA_QS;    // query sub-tiles per wavefront (see attend_kernel)
 constexpr int kMaxLists = BM / BN;   // row blocks of a query tile at the smallest block size (64): 4
 constexpr float kNegBig = -1.0e30f;

@@ -97,8 +97,12 @@ __global__ __launch_bounds__(kThreadsS, 2) void attend_split_kernel(AttendArgs a
   int z_every = 1, z_count = 1, z_passes = 1;
   if (zfill) {
     inv_row = a.inv + bkv * a.L;
-    const int tok_lo = qt == 0 ? 0 : idx_row[q0];
-    z_hi = q0 + BMS >= Lc ? a.L : idx_row[q0 + BMS];
+    // Token range of this workgroup.  Any partition of [0, L) over the query tiles of a head works (a row is
+    // cleared iff inv marks it unselected, whoever looks).  The shares grow linearly with the query tile,
+    // as the number of tile iterations does, so that every workgroup can clear its share inside its loop.
+    const long long nq = nq_tiles, wt = nq * (nq + 1) / 2;
+    const int tok_lo = (int)((long long)a.L * ((long long)qt * (qt + 1) / 2) / wt);
+    z_hi = (int)((long long)a.L * ((long long)(qt + 1) * (qt + 2) / 2) / wt);
     zrow = (u32x4*)(a.Of + a.os.head(b, h)) + (tid % LPR);
     zt = tok_lo + tid / LPR;
     zr = zt < z_hi ? inv_row[zt] : 0;
@@ -443,15 +447,26 @@ __global__ __launch_bounds__(kThreadsS, 2) void attend_split_kernel(AttendArgs a
 
   // ---- fused form: the zero rows the loop did not get to
   if (zfill) {
-    constexpr int kBatch = 8;
+    // Latency-bound: a batch of look-ups is a memory round trip.  Sixteen rows per thread and batch, the
+    // look-ups of the next batch requested before the stores of the current one (so that waiting for them
+    // never includes waiting for those stores to be acknowledged).
+    constexpr int kBatch = 16;
     if (zr < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)zt * o_pitch16);
-    for (int t0 = zt + RPP; t0 < z_hi; t0 += kBatch * RPP) {
-      int r[kBatch];
+    int t0 = zt + RPP;
+    int r[kBatch];
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j) r[j] = t0 + j * RPP < z_hi ? inv_row[t0 + j * RPP] : 0;
+    for (int j = 0; j < kBatch; ++j) r[j] = t0 + j * RPP < z_hi ? inv_row[t0 + j * RPP] : 0;
+    while (t0 < z_hi) {
+      const int t1 = t0 + kBatch * RPP;
+      int rn[kBatch];
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) rn[j] = t1 + j * RPP < z_hi ? inv_row[t1 + j * RPP] : 0;
 #pragma unroll
       for (int j = 0; j < kBatch; ++j)
         if (r[j] < 0) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, zrow + (long long)(t0 + j * RPP) * o_pitch16);
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) r[j] = rn[j];
+      t0 = t1;
     }
   }
 
