@@ -42,7 +42,10 @@ namespace {
 // every LDS fragment feeds two MFMAs.  QS = 1: 8 wavefronts of 32 rows, two per SIMD, which share
 // the SIMD's issue slots (a lone wavefront issues one vector instruction every ~8 clocks, two
 // together one every ~5) at the price of one LDS fragment per MFMA.
-template <int D, int QS, bool FUSED>
+// LISTS: the launch has a block list.  The plain causal form is a kernel of its own: the look-ups of the tile
+// generator would otherwise sit in the tile loop as loads that may be pending, and the compiler's wait for
+// them (before it reuses their registers) also waits for the K / V prefetches of the tile just requested.
+template <int D, int QS, bool FUSED, bool LISTS>
 __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) {
   constexpr int kThreads = 512 / QS;
   constexpr int RW = 32 * QS;                     // query rows per wavefront
@@ -98,7 +101,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const int q0 = qt * BM;
   const int wrow0 = q0 + RW * wave;                      // first query row of this wavefront
-  const int row_block = a.block_list ? a.block : BM;
+  const int row_block = LISTS ? a.block : BM;
   const int half_bit = 1 << ((RW * wave) / row_block);   // which row block of the query tile the wavefront is in
   const float c = a.c;
   const float c_ = c;
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0)
 
   TileGen gen;
-  gen.plain = a.block_list == nullptr;
+  gen.plain = !LISTS;
   gen.plain_i = 0;
   gen.plain_n = (min(q0 + BM, Lc) + BN - 1) / BN;
   gen.sub = gen.kb = gen.use = 0;
@@ -584,8 +587,13 @@ hipError_t launch_any(AttendArgs& a, int d, hipStream_t st) {
   a.nq_tiles = (a.Lc + BM - 1) / BM;
   a.nk_tiles = (a.Lc + BN - 1) / BN;
   const unsigned grid = 8u * (unsigned)((a.BH + 7) / 8) * (unsigned)a.nq_tiles;
-  if (d == 128) attend_kernel<128, kQS, FUSED><<<grid, 512 / kQS, 0, st>>>(a);
-  else attend_kernel<64, kQS, FUSED><<<grid, 512 / kQS, 0, st>>>(a);
+  if (a.block_list) {
+    if (d == 128) attend_kernel<128, kQS, FUSED, true><<<grid, 512 / kQS, 0, st>>>(a);
+    else attend_kernel<64, kQS, FUSED, true><<<grid, 512 / kQS, 0, st>>>(a);
+  } else {
+    if (d == 128) attend_kernel<128, kQS, FUSED, false><<<grid, 512 / kQS, 0, st>>>(a);
+    else attend_kernel<64, kQS, FUSED, false><<<grid, 512 / kQS, 0, st>>>(a);
+  }
   return hipGetLastError();
 }
 
