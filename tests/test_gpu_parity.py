@@ -46,6 +46,9 @@ def _ws(tsa, desc, k):
     (1, 2, 2, 100, 64, 100),      # window = whole sequence
     (1, 2, 1, 33, 128, 1),        # single query
     (1, 2, 2, 5000, 128, 128),    # widest window
+    (1, 8, 2, 2300, 128, 64),     # four heads per KV head (one per wavefront), several tiles per workgroup, ragged tail
+    (1, 7, 1, 1500, 64, 40),      # seven heads per KV head: two rounds over the staged tiles, the second partly idle
+    (1, 4, 1, 700, 128, 128),     # four heads per KV head with the widest window
     (1, 7, 1, 1030, 128, 64),     # last chunk holds only window keys
 ])
 def test_score(tsa, B, Hq, Hkv, L, d, Lq):
