@@ -293,6 +293,16 @@ def mfma_calibration(tsa, torch, K):
         ms = _events_ms(fn, 5, torch)
         cyc, ticks = [int(v) for v in clocks.cpu()]
         out[name] = {"tflops": flops / ms / 1e9, "shader_clock_mhz": cyc / (ticks / (khz * 1e3)) / 1e6}
+    # the instruction streams of the two matrix loops on register operands, two wavefronts per SIMD: what the
+    # loops could reach on the workload's values if staging, fragment reads and synchronisation were free
+    operands = K.reshape(-1)[: 1 << 15].contiguous()
+    mixes = {}
+    for mix, name in ((0, "attention_mfma_only"), (1, "attention_mix"), (2, "scoring_mfma_only"), (3, "scoring_mix")):
+        fn = lambda: tsa.tsa_mix_probe(mix, operands, 4000, blocks, sink)
+        flops = fn()
+        torch.cuda.synchronize()
+        mixes[name] = flops / _events_ms(fn, 5, torch) / 1e9
+    out["instruction_mix_on_workload_keys_tflops"] = mixes
     return out
 
 
@@ -343,6 +353,9 @@ def main():
     tsa.tsa_copy_probe(src, dst)
     torch.cuda.synchronize()
     hbm_copy["own_streaming_copy_gbs"] = gib2 / _events_ms(lambda: tsa.tsa_copy_probe(src, dst), 5, torch) / 1e6
+    tsa.tsa_read_probe(src, dst)
+    torch.cuda.synchronize()
+    hbm_copy["own_streaming_read_gbs"] = 0.5 * gib2 / _events_ms(lambda: tsa.tsa_read_probe(src, dst), 5, torch) / 1e6
     del src, dst
 
     head_tau = 0.75
@@ -378,7 +391,9 @@ def main():
                      "flops_per_launch": w["attend_flops"], "avg_launch_ms": head["attend_fused_ms"],
                      "traffic": profiled_traffic(),
                      "bare_mfma_loop": calib,
-                     "frac_of_bare_mfma_loop_on_workload_values": head["attend_fused_tflops"] / calib["workload_keys"]["tflops"]},
+                     "frac_of_bare_mfma_loop_on_workload_values": head["attend_fused_tflops"] / calib["workload_keys"]["tflops"],
+                     "frac_of_attention_instruction_mix_on_workload_values":
+                         head["attend_fused_tflops"] / calib["instruction_mix_on_workload_keys_tflops"]["attention_mix"]},
         "paper_context": "paper reports up to x3.23 attention speedup at 128K on one NVIDIA A100 80GB (other hardware; not a target)",
         "detail": detail,
     }

@@ -27,6 +27,23 @@ int tsa_mfma_probe(const void* operands, int32_t iters, int32_t blocks, float* s
                    double* flops, int32_t* wall_clock_khz, void* stream);
 
 
+/* Instruction-mix calibration: the MFMA and vector instruction streams of the library's two matrix loops with
+ * every operand in registers (no LDS traffic, no global memory, no barrier), two wavefronts per SIMD as in the
+ * kernels: what the loops could reach on the given operand values if staging, fragment reads and
+ * synchronisation were free.  mix 0: attention, MFMAs alone (per iteration a chain of 8 into one accumulator
+ * and 8 into four); 1: attention with its vector work (per MFMA one exp2, one add, half a pack, one fma, half
+ * a max3); 2: scoring, MFMAs alone (a chain of 8); 3: scoring with its vector work (per MFMA two fma, two
+ * exp2, two adds).  `blocks` workgroups of 4 wavefronts, each pinned to half a CU's LDS (launch 2 per CU);
+ *   operands: device, at least 16 KiB of bf16 values;  sink: device, blocks * 256 fp32 (scratch output)
+ *   flops (host, out, may be NULL): floating-point operations of the MFMAs of the whole launch
+ * The caller times the launch and divides. */
+int tsa_mix_probe(int32_t mix, const void* operands, int32_t iters, int32_t blocks, float* sink, double* flops, void* stream);
+
+/* Read-bandwidth calibration: streams `bytes` bytes (a multiple of 16, device, 16-byte aligned) through the
+ * chip without writing anything (sink: 4 bytes of device memory that are practically never written): the
+ * rate a kernel that only consumes a tensor can reach, as the scoring passes do with K. */
+int tsa_read_probe(const void* src, size_t bytes, void* sink, void* stream);
+
 /* Memory-bandwidth calibration: a plain streaming copy dst[i] = src[i] of `bytes` bytes (a multiple of
  * 16; both pointers 16-byte aligned, device) in 16-byte pieces with non-temporal stores, the access
  * pattern of the library's gather / scatter kernels without their indirection.  The caller times the

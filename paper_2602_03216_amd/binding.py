@@ -18,7 +18,7 @@ EXPORTS = ("tsa_version", "tsa_last_error", "tsa_keep_count", "tsa_workspace_byt
            "tsa_score_queries_workspace_bytes", "tsa_score_queries", "tsa_gather_queries", "tsa_pool_queries_workspace_bytes", "tsa_pool_queries",
            "tsa_select", "tsa_compress", "tsa_attend_workspace_bytes", "tsa_attend", "tsa_decompress", "tsa_compress_v_tiles", "tsa_attend_fused", "tsa_forward",
            "tsa_forward_dynamic_workspace_bytes", "tsa_forward_dynamic",
-           "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe", "tsa_copy_probe", "tsa_bench_set_attend_form",
+           "tsa_layer_drift_workspace_bytes", "tsa_layer_drift", "tsa_sparse_layers", "tsa_mfma_probe", "tsa_mix_probe", "tsa_read_probe", "tsa_copy_probe", "tsa_bench_set_attend_form",
            "tsa_select_static", "tsa_select_static_capacity")
 
 
@@ -84,6 +84,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.tsa_bench_set_attend_form.argtypes = [i32]
     lib.tsa_copy_probe.restype = ctypes.c_int
     lib.tsa_copy_probe.argtypes = [vp, vp, sz, vp]
+    lib.tsa_read_probe.restype = ctypes.c_int
+    lib.tsa_read_probe.argtypes = [vp, sz, vp, vp]
+    lib.tsa_mix_probe.restype = ctypes.c_int
+    lib.tsa_mix_probe.argtypes = [i32, vp, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.tsa_gather_queries.restype = ctypes.c_int
     lib.tsa_gather_queries.argtypes = [dp, vp, ip, i32, vp, vp]
     lib.tsa_pool_queries_workspace_bytes.restype = sz
@@ -301,6 +305,18 @@ def tsa_mfma_probe(operands, iters, blocks, sink, clocks):
     _check(load_library().tsa_mfma_probe(_ptr(operands), iters, blocks, _ptr(sink), _ptr(clocks),
                                          ctypes.byref(flops), ctypes.byref(khz), _stream()))
     return flops.value, khz.value
+
+
+def tsa_mix_probe(mix, operands, iters, blocks, sink):
+    """Queues the instruction-mix loop `mix` (0..3); returns the flops of the launch's MFMAs."""
+    flops = ctypes.c_double(0.0)
+    _check(load_library().tsa_mix_probe(mix, _ptr(operands), iters, blocks, _ptr(sink), ctypes.byref(flops), _stream()))
+    return flops.value
+
+
+def tsa_read_probe(src, sink):
+    """Queues the streaming read of src (byte size a multiple of 16); sink: a device tensor of at least 4 bytes."""
+    _check(load_library().tsa_read_probe(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()))
 
 
 def tsa_bench_set_attend_form(form: int):

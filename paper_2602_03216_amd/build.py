@@ -17,7 +17,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
 # per-file additions (attend: let the register allocator place MFMA results in VGPRs or AGPRs
 # per instruction instead of forcing every accumulator into AGPRs)
 _ATTEND_FLAGS = os.environ.get("TSA_ATTEND_FLAGS", "-mllvm -amdgpu-mfma-vgpr-form").split()
-EXTRA = {"attend.hip": _ATTEND_FLAGS, "attend_split.hip": _ATTEND_FLAGS}
+EXTRA = {"attend.hip": _ATTEND_FLAGS, "attend_split.hip": _ATTEND_FLAGS, "probe.hip": _ATTEND_FLAGS}
 _NOISE = "packed-fp32-ops"
 
 

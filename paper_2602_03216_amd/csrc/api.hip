@@ -524,6 +524,23 @@ int tsa_mfma_probe(const void* operands, int32_t iters, int32_t blocks, float* s
   return hip_status(tsa::launch_mfma_probe(operands, iters, blocks, sink, (long long*)clocks, (hipStream_t)stream), "tsa_mfma_probe");
 }
 
+int tsa_mix_probe(int32_t mix, const void* operands, int32_t iters, int32_t blocks, float* sink, double* flops, void* stream) {
+  int rc;
+  if ((rc = check_ptr(operands, "operands")) || (rc = check_ptr(sink, "sink"))) return rc;
+  if (mix < 0 || mix > 3) return fail(TSA_ERR_ARG, "mix must be 0..3");
+  if (iters < 1 || iters > (1 << 24) || blocks < 1 || blocks > 65536) return fail(TSA_ERR_ARG, "iters or blocks out of range");
+  if (flops) *flops = (double)blocks * 4.0 * (double)iters * (mix <= 1 ? 16.0 : 8.0) * (2.0 * 32 * 32 * 16);
+  return hip_status(tsa::launch_mix_probe(mix, operands, iters, blocks, sink, (hipStream_t)stream), "tsa_mix_probe");
+}
+
+int tsa_read_probe(const void* src, size_t bytes, void* sink, void* stream) {
+  int rc;
+  if ((rc = check_ptr(src, "src"))) return rc;
+  if (!sink) return fail(TSA_ERR_ARG, "sink is NULL");
+  if (bytes % 16 != 0) return fail(TSA_ERR_ARG, "bytes must be a multiple of 16");
+  return hip_status(tsa::launch_read_probe(src, bytes, sink, (hipStream_t)stream), "tsa_read_probe");
+}
+
 int tsa_bench_set_attend_form(int32_t form) {
   if (form < 0 || form > 2) return fail(TSA_ERR_ARG, "form must be 0, 1 or 2");
   tsa::set_attend_form(form);

@@ -32,6 +32,92 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const u32x4* __restrict
   }
 }
 
+// Instruction-mix calibration: the MFMA and vector instruction streams of the attention and scoring loops
+// with every operand in registers (no LDS, no global memory, no barrier), two wavefronts per SIMD as in
+// the kernels (64 KiB of LDS per workgroup of four wavefronts pins two workgroups per CU).  What this loop
+// reaches on the workload's operand values is what the kernels' loops could reach if staging, fragment
+// reads and synchronisation cost nothing: the matrix pipe waits on dependent accumulations (a chain of
+// MFMAs into one accumulator issues every ~46 clocks, not 32) and shares the SIMD's issue port with
+// the exponentials, and the clock the chip sustains drops further when vector work runs beside the MFMAs.
+//   MIX 0  attention, MFMAs alone: per unit a chain of 8 (a half tile of scores) and 8 into 4 accumulators (output)
+//   MIX 1  attention: the same with, per MFMA, one exp2, one add, half a pack (previous half tile) in the
+//          chain block and one fma, half a max3 (new half tile) in the output block
+//   MIX 2  scoring, MFMAs alone: a chain of 8 per unit
+//   MIX 3  scoring: the chain with two fma, two exp2, two adds per MFMA (previous unit)
+template <int MIX>
+__global__ __launch_bounds__(256, 2) void mix_probe_kernel(const u32x4* __restrict__ operands, float* __restrict__ sink, int iters) {
+  __shared__ char pin[64 * 1024];
+  if (iters < 0) pin[threadIdx.x] = 0;                    // never true: the array only fixes the occupancy
+  const int lane = threadIdx.x & 63;
+  bf16x8 a[8], b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = __builtin_bit_cast(bf16x8, operands[(lane + 64 * i) & 1023]);
+    b[i] = __builtin_bit_cast(bf16x8, operands[(lane + 64 * i + 512) & 1023]);
+  }
+  f32x16 o[4] = {{0}, {0}, {0}, {0}}, prev = {0}, total = {0};
+  float l = 0.f, mx = -1.0e30f, s0 = 0.f, s1 = 0.f;
+  const float c = 0.125f, m = 3.0f;
+  uint32_t pk[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+  for (int it = 0; it < iters; ++it) {
+    f32x16 nxt = {0};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      nxt = mfma32(a[i], b[i], nxt);
+      if (MIX == 1) {
+        const float p0 = fast_exp2(prev[2 * i]), p1 = fast_exp2(prev[2 * i + 1]);
+        l += p0;
+        l += p1;
+        bf16x2 v;
+        v[0] = (__bf16)p0;
+        v[1] = (__bf16)p1;
+        pk[i] = __builtin_bit_cast(uint32_t, v);
+      }
+      if (MIX == 3) {
+        s0 += fast_exp2(fmaf(prev[2 * i], c, -m));
+        s1 += fast_exp2(fmaf(prev[2 * i + 1], c, -m));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (MIX <= 1) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const u32x4 pw = {pk[4 * (i >> 2)], pk[4 * (i >> 2) + 1], pk[4 * (i >> 2) + 2], pk[4 * (i >> 2) + 3]};
+        o[i & 3] = mfma32(a[i], MIX == 1 ? __builtin_bit_cast(bf16x8, pw) : b[7 - i], o[i & 3]);
+        if (MIX == 1) {
+          mx = fmaxf(mx, fmaxf(nxt[2 * i], nxt[2 * i + 1]));
+          nxt[2 * i] = fmaf(nxt[2 * i], c, -m);
+          nxt[2 * i + 1] = fmaf(nxt[2 * i + 1], c, -m);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    prev = nxt;
+    if (MIX == 0 || MIX == 2) total += nxt;
+  }
+  float r = l + mx + s0 + s1;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) r += o[0][i] + o[1][i] + o[2][i] + o[3][i] + prev[i] + total[i];
+  sink[blockIdx.x * 256 + threadIdx.x] = r;
+}
+
+// Streaming read in 16-byte pieces, grid-stride, eight loads in flight per thread: what a kernel that only
+// consumes a tensor (the scoring passes over K) can reach.
+__global__ __launch_bounds__(256) void read_probe_kernel(const u32x4* __restrict__ src, long long n, uint32_t* __restrict__ sink) {
+  constexpr int kInFlight = 8;
+  const long long stride = (long long)gridDim.x * 256 * kInFlight;
+  u32x4 acc = {0u, 0u, 0u, 0u};
+  for (long long i = (long long)blockIdx.x * 256 * kInFlight + threadIdx.x; i < n; i += stride) {
+    u32x4 v[kInFlight];
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) v[u] = i + 256 * u < n ? __builtin_nontemporal_load(&src[i + 256 * u]) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int u = 0; u < kInFlight; ++u) acc ^= v[u];
+  }
+  const uint32_t x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+  if (x == 0x9e3779b9u) sink[0] = x;                      // keeps the loads alive; practically never stores
+}
+
 // Streaming copy in 16-byte pieces, grid-stride, non-temporal stores: what a pure mover reaches.
 __global__ __launch_bounds__(256) void copy_probe_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, long long n) {
   const long long stride = (long long)gridDim.x * 256;
@@ -47,6 +133,24 @@ hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream
   long long blocks = (n + 256 * 4 - 1) / (256 * 4);      // about four pieces per thread
   if (blocks > 65536) blocks = 65536;
   copy_probe_kernel<<<(unsigned)blocks, 256, 0, st>>>((const u32x4*)src, (u32x4*)dst, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st) {
+  const long long n = (long long)(bytes / 16);
+  if (n == 0) return hipSuccess;
+  long long blocks = (n + 256 * 8 * 4 - 1) / (256 * 8 * 4);
+  if (blocks > 16384) blocks = 16384;
+  read_probe_kernel<<<(unsigned)blocks, 256, 0, st>>>((const u32x4*)src, n, (uint32_t*)sink);
+  return hipGetLastError();
+}
+
+hipError_t launch_mix_probe(int mix, const void* operands, int iters, int blocks, float* sink, hipStream_t st) {
+  const u32x4* ops = (const u32x4*)operands;
+  if (mix == 0) mix_probe_kernel<0><<<blocks, 256, 0, st>>>(ops, sink, iters);
+  else if (mix == 1) mix_probe_kernel<1><<<blocks, 256, 0, st>>>(ops, sink, iters);
+  else if (mix == 2) mix_probe_kernel<2><<<blocks, 256, 0, st>>>(ops, sink, iters);
+  else mix_probe_kernel<3><<<blocks, 256, 0, st>>>(ops, sink, iters);
   return hipGetLastError();
 }
 

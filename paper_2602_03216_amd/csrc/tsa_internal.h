@@ -117,6 +117,11 @@ void set_attend_form(int form);
 
 // probe.hip: bare MFMA loop, 8 * iters MFMAs per wavefront, 4 wavefronts per workgroup
 hipError_t launch_mfma_probe(const void* operands, int iters, int blocks, float* sink, long long* clocks, hipStream_t st);
+// probe.hip: the MFMA / vector instruction streams of the attention (mix 0, 1) and scoring (mix 2, 3) loops on
+// register operands; 16 (mix 0, 1) or 8 (mix 2, 3) MFMAs per iteration and wavefront, 4 wavefronts per workgroup
+hipError_t launch_mix_probe(int mix, const void* operands, int iters, int blocks, float* sink, hipStream_t st);
+// probe.hip: streaming read of `bytes` bytes (a multiple of 16); sink: 4 bytes of device memory
+hipError_t launch_read_probe(const void* src, size_t bytes, void* sink, hipStream_t st);
 // probe.hip: streaming copy of `bytes` bytes (a multiple of 16)
 hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, hipStream_t st);
 

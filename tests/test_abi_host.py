@@ -78,6 +78,9 @@ def test_entry_points_reject_bad_arguments_before_any_launch(lib):
     assert lib.tsa_score_queries_workspace_bytes(dp, 0) == 0 and lib.tsa_score_queries_workspace_bytes(dp, 129) == 0
     assert lib.tsa_score_queries_workspace_bytes(dp, 100) >= lib.tsa_score_queries_workspace_bytes(dp, 3) > 0
     assert lib.tsa_copy_probe(fake, fake, 24, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_read_probe(fake, 24, fake, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_mix_probe(4, fake, 10, 8, fake, None, None) == tsa.TSA_ERR_ARG
+    assert lib.tsa_mix_probe(1, fake, 0, 8, fake, None, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_compress(dp, fake, fake, fake, None, 16, fake, fake, fake, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_attend(dp, fake, fake, fake, 0, 4, None, 0, 0, fake, None, fake, 1 << 30, None) == tsa.TSA_ERR_ARG
     assert lib.tsa_attend(dp, fake, fake, fake, 16, 3, None, 0, 0, fake, None, fake, 1 << 30, None) == tsa.TSA_ERR_ARG

@@ -48,3 +48,20 @@ def test_mfma_probe_runs_and_reports_clocks(tsa):
     mhz = cyc / (ticks / (khz * 1e3)) / 1e6
     assert cyc >= 1000 * 8 * 16 and 500 < mhz < 3500
     assert not sink.isnan().any() and float(sink.abs().max()) == 0.0      # zero operands: zero accumulators
+
+
+def test_mix_and_read_probes_run(tsa):
+    """The instruction-mix and read-bandwidth calibration loops: they queue, finish and leave finite results."""
+    ops = (torch.randn(1 << 15, device=gu.DEV) * 0.5).to(torch.bfloat16)
+    blocks = 64
+    sink = torch.empty(blocks * 256, dtype=torch.float32, device=gu.DEV)
+    for mix, per_iter in ((0, 16), (1, 16), (2, 8), (3, 8)):
+        sink.fill_(float("nan"))
+        flops = tsa.tsa_mix_probe(mix, ops, 50, blocks, sink)
+        torch.cuda.synchronize()
+        assert flops == blocks * 4 * 50 * per_iter * 2 * 32 * 32 * 16
+        assert not sink.isnan().any()                      # every thread wrote its accumulator sum
+    src = torch.arange(1 << 20, dtype=torch.int32, device=gu.DEV)
+    word = torch.zeros(1, dtype=torch.int32, device=gu.DEV)
+    tsa.tsa_read_probe(src, word)
+    torch.cuda.synchronize()
