@@ -64,9 +64,9 @@ struct ScoreArgs {
 // Lq - 1, so the padding rows of the last query sub-tile arrive as zeros without a select (nothing here
 // waits for the loads).
 template <int D, int NQT>
-__device__ __forceinline__ void load_q_frags(const ScoreArgs& a, long long bh, int lo, int hi, bf16x8 (&qf)[NQT][D / 16]) {
+__device__ __forceinline__ void load_q_frags(const ScoreArgs& a, int b, int h, int lo, int hi, bf16x8 (&qf)[NQT][D / 16]) {
   const int pitch = (int)a.qs.l * 2;
-  const __bf16* base = a.Q + a.qs.head(bh / a.Hq, bh % a.Hq) + (long long)a.q_row0 * a.qs.l;
+  const __bf16* base = a.Q + a.qs.head(b, h) + (long long)a.q_row0 * a.qs.l;
   const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, a.Lq * pitch, 0x00020000);
 #pragma unroll
   for (int qt = 0; qt < NQT; ++qt) {
@@ -376,9 +376,8 @@ __global__ __launch_bounds__(kThreads, NQT <= 2 ? 2 : 1) void score_pass1(ScoreA
   __shared__ __attribute__((aligned(1024))) __bf16 Ks[NB * G::TILE];
   __shared__ float2 red[kWaves][QP];
   const int chunk = blockIdx.x;
-  const long long bkv = blockIdx.y;
-  const int kv = (int)(bkv % a.Hkv);
-  const long long b = bkv / a.Hkv;
+  const int bkv = blockIdx.y;                            // (batch entry, KV head): 32-bit index arithmetic, no 64-bit division
+  const int kv = bkv % a.Hkv, b = bkv / a.Hkv;
   const int g = a.Hq / a.Hkv;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const WaveRole role = wave_role(g, wave);              // role.hpw == HPW (chosen by the host from g)
@@ -396,10 +395,10 @@ __global__ __launch_bounds__(kThreads, NQT <= 2 ? 2 : 1) void score_pass1(ScoreA
   for (int r0 = 0; r0 < g; r0 += role.hpw) {
     const int hh = r0 + role.hslot;
     const bool act = hh < g;
-    const long long bh = b * a.Hq + kv * g + (act ? hh : 0);
+    const int head = kv * g + (act ? hh : 0);
     bf16x8 qf[NQT][D / 16];
     __syncthreads();                                   // the previous round is done with the ring and with red[]
-    load_q_frags<D, NQT>(a, bh, lo, hi, qf);           // the Q fragments (served by the L2) ahead of the first K tiles
+    load_q_frags<D, NQT>(a, b, head, lo, hi, qf);           // the Q fragments (served by the L2) ahead of the first K tiles
     ring.start();
     float m[NQT], z[NQT];
 #pragma unroll
@@ -481,7 +480,7 @@ __global__ __launch_bounds__(kThreads, NQT <= 2 ? 2 : 1) void score_pass1(ScoreA
         for (int j = 0; j < role.ksplit; ++j) mn = fmaxf(mn, red[slot + role.hpw * j][q].x);
         float zs = 0.f;
         for (int j = 0; j < role.ksplit; ++j) zs += red[slot + role.hpw * j][q].y * fast_exp2(red[slot + role.hpw * j][q].x - mn);
-        const long long bh2 = b * a.Hq + kv * g + r0 + slot;
+        const long long bh2 = (long long)b * a.Hq + kv * g + r0 + slot;
         a.part[(bh2 * a.nchunks + chunk) * QP + q] = make_float2(mn, zs);
       }
     }
@@ -527,9 +526,8 @@ __global__ __launch_bounds__(kThreads, NQT <= 2 ? 2 : 1) void score_pass2(ScoreA
   // first read the keys pass 1 read last, which the memory-side cache still holds when K as a whole
   // (268 MB at 128K tokens x 8 KV heads) does not fit it.
   const int chunk = (int)(gridDim.x - 1 - blockIdx.x);
-  const long long bkv = gridDim.y - 1 - blockIdx.y;
-  const int kv = (int)(bkv % a.Hkv);
-  const long long b = bkv / a.Hkv;
+  const int bkv = (int)(gridDim.y - 1 - blockIdx.y);
+  const int kv = bkv % a.Hkv, b = bkv / a.Hkv;
   const int g = a.Hq / a.Hkv;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, lo = lane & 31, hi = lane >> 5;
   const WaveRole role = wave_role(g, wave);              // role.hpw == HPW (chosen by the host from g)
@@ -544,10 +542,11 @@ __global__ __launch_bounds__(kThreads, NQT <= 2 ? 2 : 1) void score_pass2(ScoreA
   for (int r0 = 0; r0 < g; r0 += role.hpw) {
     const int hh = r0 + role.hslot;
     const bool act = hh < g;
-    const long long bh = b * a.Hq + kv * g + (act ? hh : 0);
+    const int head = kv * g + (act ? hh : 0);
+    const long long bh = (long long)b * a.Hq + head;
     __syncthreads();                                   // the previous round is done with the ring
     bf16x8 qf[NQT][D / 16];
-    load_q_frags<D, NQT>(a, bh, lo, hi, qf);           // Q fragments and lse (served by the L2) ahead of the first K tiles
+    load_q_frags<D, NQT>(a, b, head, lo, hi, qf);           // Q fragments and lse (served by the L2) ahead of the first K tiles
     // log2-sum-exp of the queries this lane sees as accumulator rows
     float lse[NQT][16];
 #pragma unroll
