@@ -385,7 +385,7 @@ def main():
         "ideal_attend_speedup": head["ideal_attend_speedup"],
         "dense_ms": r128["dense_ms"],
         "hbm_copy": hbm_copy,
-        "roofline": {"kernel": "attend_kernel<128, 1, true> (tsa_attend_fused: the attention launch of tsa_forward; template arguments: d, query sub-tiles per wavefront, fused gather/scatter)",
+        "roofline": {"kernel": "attend_kernel<128, 1, true, false> (tsa_attend_fused: the attention launch of tsa_forward; template arguments: d, query sub-tiles per wavefront, fused gather/scatter, block list)",
                      "bound": "mfma", "achieved": head["attend_fused_tflops"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": head["attend_fused_frac_mfma_peak"],
                      "flops_per_launch": w["attend_flops"], "avg_launch_ms": head["attend_fused_ms"],
