@@ -343,7 +343,7 @@ int tsa_attend(const tsa_desc* desc, const void* Qc, const void* Kc, const void*
     return rc;
   if (lse && ((uintptr_t)lse & 3u)) return fail(TSA_ERR_ARG, "lse is not 4-byte aligned");
   if ((rc = check_block_list(block_list, block_size, max_blocks_per_row))) return rc;
-  if ((long long)((dm.B * dm.Hq + 7) / 8) * 8 * ((Lc + 127) / 128) > 0x7fffffffLL)
+  if ((long long)dm.B * dm.Hq * ((Lc + 127) / 128 + 7) > 0x7fffffffLL)      // upper bound of the launch's workgroups
     return fail(TSA_ERR_UNSUPPORTED, "grid too large");
   if ((rc = check_ws(ws, ws_bytes, tsa::v_tiles_bytes(dm.B, kv_heads, Lc, dm.d)))) return rc;
   hipStream_t st = (hipStream_t)stream;

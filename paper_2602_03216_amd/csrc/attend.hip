@@ -63,10 +63,9 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
   // id % 8 picks the XCD; all tiles of a head (and all heads of a KV group) stay on one XCD to
   // share its L2, and the longest (last) query tiles are scheduled first.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int heads_per_xcd = (a.BH + 7) >> 3;
-  const int hp = (slot % heads_per_xcd) * 8 + xcd;
-  if (hp >= a.BH) return;
-  const int b = hp / a.Hq, hr = hp % a.Hq;
+  const int vhead = xcd * a.vheads_per_xcd + slot % a.vheads_per_xcd;
+  const int hp = vhead / a.head_split, part = vhead % a.head_split;
+  const int b = hp / a.Hq, h = hp % a.Hq;
   // Rows of this batch entry's compacted set: the launch's count, or (fused form with a coverage
   // budget decided on the device) the count read from k_dev; a.Lc stays the capacity, i.e. the row
   // stride of idx and of the tile arrays, and the grid is sized for it.
@@ -75,11 +74,10 @@ __global__ __launch_bounds__(512 / QS, 2 / QS) void attend_kernel(AttendArgs a) 
     Lc = a.k_dev[b];
     nq_tiles = (Lc + BM - 1) / BM;
   }
-  const int qt = nq_tiles - 1 - slot / heads_per_xcd;
+  const int qt = nq_tiles - 1 - ((slot / a.vheads_per_xcd) * a.head_split + part);
   if (qt < 0) return;
   const int g = a.Hq / a.kvh;
   const int n_grp = FUSED ? a.Hkv : a.kvh, g_grp = a.Hq / n_grp;
-  const int h = (hr % n_grp) * g_grp + hr / n_grp;       // heads of one KV group are 8 apart in hp
   const long long bh = (long long)b * a.Hq + h;
   const long long bkv = (long long)b * a.kvh + h / g;    // head of K^ / V^ (fused: of the index set and the V tiles)
   // rows of Q and K: the compacted tensors, or (fused) the original ones addressed through idx
@@ -586,7 +584,8 @@ hipError_t launch_any(AttendArgs& a, int d, hipStream_t st) {
   if (kQS == 1 && use_split_form(a)) return launch_attend_split(a, d, FUSED, st);
   a.nq_tiles = (a.Lc + BM - 1) / BM;
   a.nk_tiles = (a.Lc + BN - 1) / BN;
-  const unsigned grid = 8u * (unsigned)((a.BH + 7) / 8) * (unsigned)a.nq_tiles;
+  map_workgroups(a);
+  const unsigned grid = grid_for(a);
   if (a.block_list) {
     if (d == 128) attend_kernel<128, kQS, FUSED, true><<<grid, 512 / kQS, 0, st>>>(a);
     else attend_kernel<64, kQS, FUSED, true><<<grid, 512 / kQS, 0, st>>>(a);

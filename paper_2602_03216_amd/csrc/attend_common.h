@@ -39,6 +39,7 @@ struct AttendArgs {
   int max_blocks;
   int block;                   // block size of the list: 64, 128 or 256 tokens
   int BH, Hq, kvh, Lc, nq_tiles, nk_tiles;
+  int head_split, vheads_per_xcd;   // workgroup -> (head, query tile) map, see map_workgroups()
   const int32_t* k_dev;        // fused form: compacted rows per batch entry, decided on the device (NULL: Lc)
   Strides qs, ks, os;          // fused form: layouts of the original Q, K and of the full-length output (elements)
   float c;                     // scale * log2(e)
@@ -57,6 +58,24 @@ struct AttendArgs {
   __bf16* X;
   int L, Hkv;
 };
+
+// Workgroup -> (head, query tile).  Consecutive workgroup ids go to different XCDs, so id % 8 picks the XCD.
+// A head's query tiles stay on one XCD (they stream the same K / V through its L2), consecutive heads (the
+// heads of a KV group) share an XCD, and the longest (last) query tiles are scheduled first.  When the number
+// of heads is no multiple of 8, whole heads per XCD would leave some XCDs with one head more than others (28
+// heads: four against three, a launch 14 % longer than its work); every head is then cut into `head_split`
+// parts (query tiles qt with (nq - 1 - qt) % head_split == part), so that the B * Hq * head_split parts
+// divide evenly: XCD x takes parts [x * vheads_per_xcd, (x + 1) * vheads_per_xcd), i.e. whole heads and at
+// most two partial ones.
+inline void map_workgroups(AttendArgs& a) {
+  int g = 8;
+  while (a.BH % g) g >>= 1;                       // gcd(BH, 8)
+  a.head_split = 8 / g;
+  a.vheads_per_xcd = a.BH / g;
+}
+inline unsigned grid_for(const AttendArgs& a) {
+  return 8u * (unsigned)a.vheads_per_xcd * (unsigned)((a.nq_tiles + a.head_split - 1) / a.head_split);
+}
 
 // two bf16 in one dword: widen to fp32 (exact), add, round each sum to bf16 (nearest even)
 __device__ __forceinline__ uint32_t add_bf16_pairs(uint32_t x, uint32_t o) {

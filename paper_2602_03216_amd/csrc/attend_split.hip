@@ -49,20 +49,18 @@ __global__ __launch_bounds__(kThreadsS, 2) void attend_split_kernel(AttendArgs a
   __shared__ __attribute__((aligned(16))) __bf16 smem[NKT * KTILE + NVT * VTILE];
 
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int heads_per_xcd = (a.BH + 7) >> 3;
-  const int hp = (slot % heads_per_xcd) * 8 + xcd;
-  if (hp >= a.BH) return;
-  const int b = hp / a.Hq, hr = hp % a.Hq;
+  const int vhead = xcd * a.vheads_per_xcd + slot % a.vheads_per_xcd;
+  const int hp = vhead / a.head_split, part = vhead % a.head_split;
+  const int b = hp / a.Hq, h = hp % a.Hq;
   int Lc = a.Lc, nq_tiles = a.nq_tiles;
   if (FUSED && a.k_dev) {
     Lc = a.k_dev[b];
     nq_tiles = (Lc + BMS - 1) / BMS;
   }
-  const int qt = nq_tiles - 1 - slot / heads_per_xcd;
+  const int qt = nq_tiles - 1 - ((slot / a.vheads_per_xcd) * a.head_split + part);
   if (qt < 0) return;
   const int g = a.Hq / a.kvh;
   const int n_grp = FUSED ? a.Hkv : a.kvh, g_grp = a.Hq / n_grp;
-  const int h = (hr % n_grp) * g_grp + hr / n_grp;
   const long long bh = (long long)b * a.Hq + h;
   const long long bkv = (long long)b * a.kvh + h / g;
   const int q_pitch = FUSED ? (int)a.qs.l * 2 : ROWB, k_pitch = FUSED ? (int)a.ks.l * 2 : ROWB;
@@ -535,7 +533,8 @@ __global__ __launch_bounds__(kThreadsS, 2) void attend_split_kernel(AttendArgs a
 hipError_t launch_attend_split(AttendArgs& a, int d, bool fused, hipStream_t st) {
   a.nq_tiles = (a.Lc + BMS - 1) / BMS;
   a.nk_tiles = (a.Lc + BN - 1) / BN;
-  const unsigned grid = 8u * (unsigned)((a.BH + 7) / 8) * (unsigned)a.nq_tiles;
+  map_workgroups(a);
+  const unsigned grid = grid_for(a);
   if (d == 128) {
     if (fused) attend_split_kernel<128, true><<<grid, kThreadsS, 0, st>>>(a);
     else attend_split_kernel<128, false><<<grid, kThreadsS, 0, st>>>(a);
